@@ -1,0 +1,114 @@
+"""ctypes front-end of the CPU oracle (``spec_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg, never by the product package.  It compiles the
+C file with gcc on first use (or through ``build()``) and marshals numpy arrays;
+all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spec_oracle.c")
+_LIB = os.path.join(_HERE, "libspec_oracle.so")
+_DT = {"f32": 0, "bf16": 1, "fp8": 2}
+OUT_WIDTH = 9  # draft depth is at most 8, so at most 9 tokens come out per request
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP only for the outer request loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.oracle_verify_attn.restype = ctypes.c_int
+        lib.oracle_spec_accept.restype = ctypes.c_int
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_decode.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return ctypes.c_void_p(0)
+    assert a.flags["C_CONTIGUOUS"]
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def decode(x: np.ndarray, dtype: str) -> np.ndarray:
+    x = np.ascontiguousarray(x)
+    out = np.empty(x.shape, dtype=np.float64)
+    _load().oracle_decode(_p(x), ctypes.c_int64(x.size), ctypes.c_int(_DT[dtype]), _p(out))
+    return out
+
+
+def verify_attn(inp: Dict[str, object], *, part_tokens: int = 0,
+                requests: Optional[Sequence[int]] = None, threads: int = 0):
+    """Run the attention oracle on a batch dict from ``synth.make_attention_inputs``.
+
+    Returns (out[R,Hq,D] float64, lse[R,Hq] float64); rows of requests not in
+    ``requests`` are NaN.
+    """
+    lib = _load()
+    R, Hq, D = inp["total_rows"], inp["num_q_heads"], inp["head_dim"]
+    out = np.full((R, Hq, D), np.nan, dtype=np.float64)
+    lse = np.full((R, Hq), np.nan, dtype=np.float64)
+    req = None if requests is None else np.ascontiguousarray(requests, dtype=np.int32)
+    rc = lib.oracle_verify_attn(
+        ctypes.c_int(inp["batch"]), ctypes.c_int(Hq), ctypes.c_int(inp["num_kv_heads"]),
+        ctypes.c_int(D), ctypes.c_int(inp["block_size"]), ctypes.c_int(inp["max_blocks_per_seq"]),
+        ctypes.c_int(_DT[inp["kv_dtype"]]), _p(inp["k_cache"]), _p(inp["v_cache"]),
+        _p(inp["k_scale"]), _p(inp["v_scale"]), _p(inp["block_table"]), _p(inp["kv_len"]),
+        _p(inp["q_indptr"]), ctypes.c_int(_DT[inp["q_dtype"]]), _p(inp["q"]),
+        ctypes.c_double(inp["sm_scale"]), ctypes.c_int(part_tokens), _p(req),
+        ctypes.c_int(0 if req is None else len(req)), _p(out), _p(lse), ctypes.c_int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle_verify_attn rejected its arguments (code {rc})")
+    return out, lse
+
+
+def spec_accept(inp: Dict[str, object], *, greedy: Optional[bool] = None, tie_eps: float = 1e-5,
+                threads: int = 0) -> Dict[str, np.ndarray]:
+    """Run the acceptance oracle on a batch dict from ``synth.make_accept_inputs``."""
+    lib = _load()
+    B, R = inp["batch"], inp["total_rows"]
+    Rd = R - B
+    g = inp["greedy"] if greedy is None else int(greedy)
+    accepted = np.full(B, -99, dtype=np.int32)
+    toks = np.full((B, OUT_WIDTH), -99, dtype=np.int32)
+    ratio = np.full(max(Rd, 1), np.nan, dtype=np.float64)
+    near = np.zeros(max(Rd, 1), dtype=np.int32)
+    ylo = np.full(B, -1, dtype=np.int32)
+    yhi = np.full(B, -1, dtype=np.int32)
+    rsum = np.full(B, np.nan, dtype=np.float64)
+    rc = lib.oracle_spec_accept(
+        ctypes.c_int(B), ctypes.c_int(inp["vocab"]), ctypes.c_int64(inp["row_stride"]),
+        ctypes.c_int(_DT[inp["logit_dtype"]]), _p(inp["q_indptr"]), _p(inp["target_logits"]),
+        _p(inp["draft_logits"]), _p(inp["draft_tokens"]), _p(inp["u_accept"]), _p(inp["u_sample"]),
+        _p(inp["temperature"]), ctypes.c_int(g), ctypes.c_int(OUT_WIDTH), ctypes.c_double(tie_eps),
+        _p(accepted), _p(toks), _p(ratio), _p(near), _p(ylo), _p(yhi), _p(rsum),
+        ctypes.c_int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle_spec_accept rejected its arguments (code {rc})")
+    return dict(accepted_len=accepted, out_tokens=toks, ratio=ratio[:Rd], near_tie=near[:Rd],
+                y_lo=ylo, y_hi=yhi, resid_sum=rsum)

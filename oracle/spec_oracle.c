@@ -1,0 +1,431 @@
+/*
+ * CPU oracle for the decode lane's speculative-verification step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the GPU library must compute.  It shares no code, header, table or constant
+ * with the HIP path, and only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it.
+ *
+ * What the paper fixes: the decode worker verifies a request's draft tokens in
+ * one parallel target-model pass while preserving the target's output
+ * distribution (Section 2.2, the speculative-sampling rule of the work cited
+ * there), over a paged KV cache (Section 2.4) that holds the prefill KV with
+ * every decoded token appended (Section 3.4, Eq. 7); the depth of each request
+ * is chosen per request by the controller (Section 3.5, Alg. 4, Eq. 13).  The
+ * paper gives no further detail of the verification itself, so the functions
+ * below write out the textbook definitions; every reading taken where the
+ * paper is silent is listed in the repository's design notes.
+ *
+ * All floating point is IEEE double.  Inputs arrive in their storage format
+ * (float32, bfloat16 bits, OCP e4m3fn bytes) and are decoded here, exactly.
+ *
+ * Pin status: every function in this file is pinned by tests/test_oracle_*.py
+ * (library attention routine, brute force, closed forms, exhaustive
+ * enumeration of the sampling identity).  Accepted-length statistics on the
+ * five workloads are "parity unpinned" by the paper (it prints none).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { OR_F32 = 0, OR_BF16 = 1, OR_FP8_E4M3 = 2 };
+
+/* ---- exact storage decoders ------------------------------------------------ */
+
+static double decode_bf16(uint16_t h)
+{
+    uint32_t w = (uint32_t)h << 16; /* bfloat16 is the upper half of a float32 */
+    float f;
+    memcpy(&f, &w, 4);
+    return (double)f;
+}
+
+/* OCP 8-bit float, 1 sign / 4 exponent (bias 7) / 3 mantissa bits, "fn" flavour:
+ * no infinities, the single NaN pattern is S.1111.111, largest finite is 448. */
+static double decode_e4m3fn(uint8_t b)
+{
+    int sign = b >> 7, e = (b >> 3) & 0xF, m = b & 0x7;
+    double v;
+    if (e == 0xF && m == 0x7)
+        return NAN;
+    if (e == 0)
+        v = ldexp((double)m / 8.0, -6); /* subnormal: 2^(1-7) * m/8 */
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+static double load_elem(const void *base, int64_t idx, int dtype)
+{
+    switch (dtype) {
+    case OR_F32:
+        return (double)((const float *)base)[idx];
+    case OR_BF16:
+        return decode_bf16(((const uint16_t *)base)[idx]);
+    default:
+        return decode_e4m3fn(((const uint8_t *)base)[idx]);
+    }
+}
+
+/* for tests: decode n elements of a storage array */
+void oracle_decode(const void *src, int64_t n, int dtype, double *dst)
+{
+    for (int64_t i = 0; i < n; ++i)
+        dst[i] = load_elem(src, i, dtype);
+}
+
+/* ---- verify attention -------------------------------------------------------
+ *
+ * Request b brings q_len = q_indptr[b+1]-q_indptr[b] = k_b+1 query tokens: the
+ * last accepted token followed by its k_b draft tokens.  Their keys/values are
+ * already the last q_len of the kv_len[b] valid cache positions, so query
+ * token i sits at absolute position pos_i = kv_len - q_len + i and attends to
+ * cache positions 0..pos_i (causal among the new tokens, everything older is
+ * visible).  Query head h reads KV head h / (Hq/Hkv).
+ *
+ *     s_t = sm_scale * <Q[row,h,:], K[t,:]>        t = 0..pos_i
+ *     out = sum_t softmax(s)_t * V[t,:]            lse = ln sum_t exp(s_t)
+ *
+ * Cache position t of request b lives in physical block block_table[b][t/bs],
+ * slot t%bs; element (block, kv head, slot, d) of the dense cache array.  For
+ * e4m3 caches the real value is decode(byte) * scale[block][kv head].
+ *
+ * part_tokens > 0 computes the same thing the split way: the visible range is
+ * cut into pieces of part_tokens positions, each piece yields its own
+ * softmax-weighted value sum and log-sum-exp, and the pieces are merged with
+ *     lse = ln sum_p exp(lse_p),   out = sum_p exp(lse_p - lse) * out_p.
+ * Both ways must agree to rounding; a test checks that.
+ *
+ * req_list (may be NULL = all) selects which requests to compute; rows of the
+ * other requests are left untouched.  Returns 0, or a negative code on bad
+ * arguments (checked before any work).
+ */
+static void attend_range(const double *qrow, int D, int dtype, const void *kc, const void *vc,
+                         const float *k_scale, const float *v_scale, const int32_t *bt_row,
+                         int Hkv, int g, int bs, int t0, int t1, double sm_scale,
+                         double *s /*scratch t1-t0*/, double *out /*D*/, double *lse)
+{
+    double m = -INFINITY;
+    for (int t = t0; t < t1; ++t) {
+        int64_t phys = bt_row[t / bs];
+        int64_t base = ((phys * Hkv + g) * bs + (t % bs)) * (int64_t)D;
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d)
+            acc += qrow[d] * load_elem(kc, base + d, dtype);
+        if (k_scale)
+            acc *= (double)k_scale[phys * Hkv + g];
+        s[t - t0] = sm_scale * acc;
+        if (s[t - t0] > m)
+            m = s[t - t0];
+    }
+    double l = 0.0;
+    for (int t = t0; t < t1; ++t) {
+        s[t - t0] = exp(s[t - t0] - m);
+        l += s[t - t0];
+    }
+    for (int d = 0; d < D; ++d)
+        out[d] = 0.0;
+    for (int t = t0; t < t1; ++t) {
+        int64_t phys = bt_row[t / bs];
+        int64_t base = ((phys * Hkv + g) * bs + (t % bs)) * (int64_t)D;
+        double w = s[t - t0] / l;
+        if (v_scale)
+            w *= (double)v_scale[phys * Hkv + g];
+        for (int d = 0; d < D; ++d)
+            out[d] += w * load_elem(vc, base + d, dtype);
+    }
+    *lse = m + log(l);
+}
+
+int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, int kv_dtype,
+                       const void *k_cache, const void *v_cache, const float *k_scale,
+                       const float *v_scale, const int32_t *block_table, const int32_t *kv_len,
+                       const int32_t *q_indptr, int q_dtype, const void *q, double sm_scale,
+                       int part_tokens, const int32_t *req_list, int n_req, double *out,
+                       double *lse, int num_threads)
+{
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || D <= 0 || bs <= 0 || part_tokens < 0)
+        return -1;
+    if (kv_dtype < 0 || kv_dtype > 2 || q_dtype < 0 || q_dtype > 1)
+        return -2;
+    if ((kv_dtype == OR_FP8_E4M3) != (k_scale != NULL) || (k_scale == NULL) != (v_scale == NULL))
+        return -3;
+    for (int b = 0; b < B; ++b) {
+        int ql = q_indptr[b + 1] - q_indptr[b];
+        if (ql < 1 || kv_len[b] < ql || (kv_len[b] + bs - 1) / bs > max_blocks)
+            return -4;
+    }
+    int G = Hq / Hkv;
+    int n = req_list ? n_req : B;
+    int fail = 0;
+#ifdef _OPENMP
+    if (num_threads > 0)
+        omp_set_num_threads(num_threads);
+#endif
+    (void)num_threads;
+    /* one unit of parallel work = (request, query head); the arithmetic inside is sequential */
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int ib = 0; ib < n; ++ib) {
+        for (int h = 0; h < Hq; ++h) {
+            int b = req_list ? req_list[ib] : ib;
+            int ql = q_indptr[b + 1] - q_indptr[b];
+            int L = kv_len[b];
+            int g = h / G;
+            const int32_t *bt_row = block_table + (int64_t)b * max_blocks;
+            double *s = (double *)malloc(sizeof(double) * (size_t)L);
+            double *qrow = (double *)malloc(sizeof(double) * (size_t)D * 3);
+            if (!s || !qrow) {
+                fail = 1;
+                free(s);
+                free(qrow);
+                continue;
+            }
+            double *o_part = qrow + D, *o_sum = qrow + 2 * D;
+            for (int i = 0; i < ql; ++i) {
+                int64_t row = q_indptr[b] + i;
+                int vis = L - ql + i + 1; /* positions 0..pos_i */
+                double *o = out + (row * Hq + h) * (int64_t)D;
+                for (int d = 0; d < D; ++d)
+                    qrow[d] = load_elem(q, (row * Hq + h) * (int64_t)D + d, q_dtype);
+                if (part_tokens == 0) {
+                    attend_range(qrow, D, kv_dtype, k_cache, v_cache, k_scale, v_scale, bt_row,
+                                 Hkv, g, bs, 0, vis, sm_scale, s, o, &lse[row * Hq + h]);
+                } else {
+                    /* split into pieces, then merge the pieces by their log-sum-exp */
+                    int np = (vis + part_tokens - 1) / part_tokens;
+                    double *pl = (double *)malloc(sizeof(double) * (size_t)np);
+                    double *po = (double *)malloc(sizeof(double) * (size_t)np * D);
+                    double mx = -INFINITY, tot = 0.0;
+                    for (int p = 0; p < np; ++p) {
+                        int t0 = p * part_tokens;
+                        int t1 = t0 + part_tokens < vis ? t0 + part_tokens : vis;
+                        attend_range(qrow, D, kv_dtype, k_cache, v_cache, k_scale, v_scale,
+                                     bt_row, Hkv, g, bs, t0, t1, sm_scale, s, o_part, &pl[p]);
+                        memcpy(po + (size_t)p * D, o_part, sizeof(double) * D);
+                        if (pl[p] > mx)
+                            mx = pl[p];
+                    }
+                    for (int p = 0; p < np; ++p)
+                        tot += exp(pl[p] - mx);
+                    double L_all = mx + log(tot);
+                    for (int d = 0; d < D; ++d)
+                        o_sum[d] = 0.0;
+                    for (int p = 0; p < np; ++p) {
+                        double w = exp(pl[p] - L_all);
+                        for (int d = 0; d < D; ++d)
+                            o_sum[d] += w * po[(size_t)p * D + d];
+                    }
+                    memcpy(o, o_sum, sizeof(double) * D);
+                    lse[row * Hq + h] = L_all;
+                    free(pl);
+                    free(po);
+                }
+            }
+            free(s);
+            free(qrow);
+        }
+    }
+    return fail ? -5 : 0;
+}
+
+/* ---- acceptance / resampling -------------------------------------------------
+ *
+ * Per request b with depth k (k+1 target rows lp_0..lp_k, k draft rows
+ * lq_0..lq_{k-1}, draft tokens x_0..x_{k-1}, uniforms u_0..u_{k-1} and u_s,
+ * temperature T > 0):
+ *
+ *     p_i = softmax(lp_i / T),  q_i = softmax(lq_i / T)
+ *     walk i = 0,1,..: accept draft i iff  u_i * q_i[x_i] < p_i[x_i]
+ *                      (that is u_i < min(1, p/q)); stop at the first rejection
+ *     n = number accepted
+ *     n < k : r = max(0, p_n - q_n)   (residual of the rejected position)
+ *     n = k : r = p_k                 (bonus distribution)
+ *     S = sum_v r_v,  c_v = r_0 + .. + r_v in token order,
+ *     y = the first v with c_v > u_s * S   (never a zero-mass token);
+ *         if rounding leaves none, the last v with r_v > 0;
+ *         if S == 0 (p_n == q_n exactly), the lowest-index argmax of lp_n
+ *     emit x_0..x_{n-1}, y;  accepted_len = n
+ *
+ * Greedy mode ignores T and the uniforms: accept while the lowest-index argmax
+ * of lp_i equals x_i; y is the lowest-index argmax of lp_n.
+ *
+ * Row placement: target rows of request b are q_indptr[b] .. q_indptr[b+1]-1 of
+ * a [rows][row_stride] array; its draft rows, tokens and u_i start at
+ * q_indptr[b] - b of the draft-side arrays.
+ *
+ * Diagnostics for the comparison harness (none feeds back into the result):
+ *   ratio[j]     p/q of every draft position j (also those after the rejection)
+ *   near_tie[j]  1 where |u_j - min(1,p/q)| < tie_eps: the one place where the
+ *                test statement allows a GPU result to differ
+ *   y_lo/y_hi[b] the tokens whose CDF interval [c_{v-1}, c_v]/S comes within
+ *                tie_eps of u_s (zero-mass tokens skipped); y_lo <= y <= y_hi
+ *   resid_sum[b] S
+ */
+static void softmax_row(const void *logits, int64_t off, int V, int dtype, double T, double *p)
+{
+    double m = -INFINITY, z = 0.0;
+    for (int v = 0; v < V; ++v) {
+        p[v] = load_elem(logits, off + v, dtype) / T;
+        if (p[v] > m)
+            m = p[v];
+    }
+    for (int v = 0; v < V; ++v) {
+        p[v] = exp(p[v] - m);
+        z += p[v];
+    }
+    for (int v = 0; v < V; ++v)
+        p[v] /= z;
+}
+
+static int argmax_row(const void *logits, int64_t off, int V, int dtype)
+{
+    int best = 0;
+    double bv = load_elem(logits, off, dtype);
+    for (int v = 1; v < V; ++v) {
+        double x = load_elem(logits, off + v, dtype);
+        if (x > bv) { /* strict: ties keep the lowest index */
+            bv = x;
+            best = v;
+        }
+    }
+    return best;
+}
+
+int oracle_spec_accept(int B, int V, int64_t row_stride, int logit_dtype, const int32_t *q_indptr,
+                       const void *target_logits, const void *draft_logits,
+                       const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                       const float *temperature, int greedy, int width, double tie_eps,
+                       int32_t *accepted_len, int32_t *out_tokens, double *ratio,
+                       int32_t *near_tie, int32_t *y_lo, int32_t *y_hi, double *resid_sum,
+                       int num_threads)
+{
+    if (B < 0 || V <= 0 || row_stride < V || logit_dtype < 0 || logit_dtype > 1 || width < 1)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (k < 0 || k + 1 > width)
+            return -4;
+        if (!greedy && !(temperature[b] > 0.0f))
+            return -6;
+        for (int i = 0; i < k; ++i) {
+            int x = draft_tokens[q_indptr[b] - b + i];
+            if (x < 0 || x >= V)
+                return -7;
+        }
+    }
+    int fail = 0;
+#ifdef _OPENMP
+    if (num_threads > 0)
+        omp_set_num_threads(num_threads);
+#endif
+    (void)num_threads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        int64_t trow0 = q_indptr[b], drow0 = q_indptr[b] - b;
+        int32_t *toks = out_tokens + (int64_t)b * width;
+        for (int j = 0; j < width; ++j)
+            toks[j] = -1;
+        if (greedy) {
+            int n = 0;
+            while (n < k &&
+                   argmax_row(target_logits, (trow0 + n) * row_stride, V, logit_dtype) ==
+                       draft_tokens[drow0 + n])
+                ++n;
+            for (int j = 0; j < n; ++j)
+                toks[j] = draft_tokens[drow0 + j];
+            toks[n] = argmax_row(target_logits, (trow0 + n) * row_stride, V, logit_dtype);
+            accepted_len[b] = n;
+            for (int j = 0; j < k; ++j) {
+                if (ratio) ratio[drow0 + j] = NAN;
+                if (near_tie) near_tie[drow0 + j] = 0;
+            }
+            if (y_lo) y_lo[b] = toks[n];
+            if (y_hi) y_hi[b] = toks[n];
+            if (resid_sum) resid_sum[b] = NAN;
+            continue;
+        }
+        double T = (double)temperature[b];
+        double *p = (double *)malloc(sizeof(double) * (size_t)V * 2);
+        if (!p) {
+            fail = 1;
+            continue;
+        }
+        double *q = p + V;
+        int n = k; /* becomes the index of the first rejection */
+        for (int i = 0; i < k; ++i) {
+            softmax_row(target_logits, (trow0 + i) * row_stride, V, logit_dtype, T, p);
+            softmax_row(draft_logits, (drow0 + i) * row_stride, V, logit_dtype, T, q);
+            int x = draft_tokens[drow0 + i];
+            double u = (double)u_accept[drow0 + i];
+            int accept = u * q[x] < p[x];
+            if (!accept && n == k)
+                n = i;
+            double rho = p[x] / q[x]; /* inf if q underflowed to 0 < p; nan if 0/0 */
+            if (ratio) ratio[drow0 + i] = rho;
+            if (near_tie) {
+                double capped = rho < 1.0 ? rho : 1.0;
+                near_tie[drow0 + i] = (rho == rho) && fabs(u - capped) < tie_eps && rho < 1.0 + tie_eps;
+            }
+        }
+        /* distribution to draw the one new token from */
+        softmax_row(target_logits, (trow0 + n) * row_stride, V, logit_dtype, T, p);
+        if (n < k) {
+            softmax_row(draft_logits, (drow0 + n) * row_stride, V, logit_dtype, T, q);
+            for (int v = 0; v < V; ++v)
+                p[v] = p[v] > q[v] ? p[v] - q[v] : 0.0;
+        }
+        double S = 0.0;
+        for (int v = 0; v < V; ++v)
+            S += p[v];
+        int y = -1, lo = -1, hi = -1;
+        if (S > 0.0) {
+            double thr = (double)u_sample[b] * S, c = 0.0, us = (double)u_sample[b];
+            int last_pos = -1;
+            for (int v = 0; v < V; ++v) {
+                if (!(p[v] > 0.0))
+                    continue;
+                double c_prev = c;
+                c += p[v];
+                last_pos = v;
+                if (y < 0 && c > thr)
+                    y = v;
+                /* does [c_prev, c]/S come within tie_eps of u_s ? */
+                if (c_prev / S - tie_eps <= us && us <= c / S + tie_eps) {
+                    if (lo < 0) lo = v;
+                    hi = v;
+                }
+            }
+            if (y < 0)
+                y = last_pos;
+            if (lo < 0) lo = hi = y;
+            if (y < lo) lo = y;
+            if (y > hi) hi = y;
+        } else {
+            y = lo = hi = argmax_row(target_logits, (trow0 + n) * row_stride, V, logit_dtype);
+        }
+        for (int j = 0; j < n; ++j)
+            toks[j] = draft_tokens[drow0 + j];
+        toks[n] = y;
+        accepted_len[b] = n;
+        if (y_lo) y_lo[b] = lo;
+        if (y_hi) y_hi[b] = hi;
+        if (resid_sum) resid_sum[b] = S;
+        free(p);
+    }
+    return fail ? -5 : 0;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,320 @@
+"""Pins for the acceptance/resampling oracle (CPU only).
+
+The key pin is the speculative-sampling identity (the property the paper's
+Section 2.2 relies on: verification preserves the target's output
+distribution): on tiny vocabularies the distribution of every emitted token is
+enumerated exactly and must equal the target distribution.  Other tests fix
+the greedy rule, special cases with known answers, library inverse-CDF
+sampling, closed forms and invariances.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2604_09562_amd import synth
+from tests.helpers import softmax64
+
+TINY = synth.CONFIGS[0]
+W = 9
+
+
+def _batch(tgt_rows, drf_rows, tokens, u_acc, u_s, depths, T=1.0, greedy=0, dtype="f32"):
+    """Assemble an accept batch from explicit per-request pieces (lists over requests)."""
+    depths = np.asarray(depths, dtype=np.int32)
+    B = len(depths)
+    q_indptr = np.zeros(B + 1, np.int32)
+    q_indptr[1:] = np.cumsum(depths + 1)
+    tgt = np.concatenate([np.asarray(t, np.float32).reshape(d + 1, -1) for t, d in zip(tgt_rows, depths)])
+    V = tgt.shape[1]
+    dl = [np.asarray(t, np.float32).reshape(d, V) for t, d in zip(drf_rows, depths)]
+    drf = np.concatenate(dl) if len(dl) and sum(depths) else np.zeros((0, V), np.float32)
+    cat = lambda xs, dt: (np.concatenate([np.asarray(x, dt).reshape(-1) for x in xs])
+                          if sum(depths) else np.zeros(0, dt))
+    temp = np.full(B, T, np.float32) if np.isscalar(T) else np.asarray(T, np.float32)
+    return dict(batch=B, vocab=V, row_stride=V, logit_dtype=dtype, total_rows=int(q_indptr[-1]),
+                depth=depths, q_indptr=q_indptr, target_logits=synth.store(tgt, dtype),
+                draft_logits=synth.store(drf, dtype), draft_tokens=cat(tokens, np.int32),
+                u_accept=cat(u_acc, np.float32), u_sample=np.asarray(u_s, np.float32),
+                temperature=temp, greedy=greedy)
+
+
+# ----------------------------------------------------------------------------- greedy
+def test_greedy_is_longest_prefix_matching_target_argmax(oracle):
+    cfg = TINY.scaled(batch=64, vocab=50, depth=("uniform", 0, 8), sigma_draft=("fixed", 0.3),
+                      logit_dtype="bf16")   # bf16 + small vocab: argmax ties do occur
+    inp = synth.make_accept_inputs(cfg, seed=0, greedy=True)
+    res = oracle.spec_accept(inp)
+    tgt = synth.decode_storage(inp["target_logits"], "bf16")
+    ties = 0
+    for b in range(inp["batch"]):
+        k = int(inp["depth"][b])
+        r0, d0 = inp["q_indptr"][b], inp["q_indptr"][b] - b
+        am = [int(np.argmax(tgt[r0 + i])) for i in range(k + 1)]     # numpy: first maximal index
+        ties += sum(int((tgt[r0 + i] == tgt[r0 + i].max()).sum() > 1) for i in range(k + 1))
+        x = inp["draft_tokens"][d0:d0 + k]
+        n = 0
+        while n < k and x[n] == am[n]:
+            n += 1
+        assert res["accepted_len"][b] == n
+        expect = list(x[:n]) + [am[n]] + [-1] * (W - n - 1)
+        assert res["out_tokens"][b].tolist() == expect
+    assert ties > 0, "the case should exercise tie-breaking"
+    assert 0 < res["accepted_len"].sum() < inp["depth"].sum()
+
+
+# ----------------------------------------------------------------------------- exact identity
+def _cells(breaks):
+    """Midpoints and widths of the intervals that sorted breakpoints cut [0,1) into."""
+    pts = np.unique(np.clip(np.concatenate([[0.0, 1.0], breaks]), 0.0, 1.0))
+    mid, wid = (pts[1:] + pts[:-1]) / 2, pts[1:] - pts[:-1]
+    keep = wid > 1e-6  # float32 uniforms cannot resolve narrower cells; their mass is below the tolerance
+    return mid[keep], wid[keep]
+
+
+@pytest.mark.parametrize("V,k,T,seed", [(4, 1, 1.0, 0), (8, 1, 0.7, 1), (5, 2, 1.3, 2), (8, 2, 1.0, 3), (3, 2, 0.5, 4)])
+def test_sampling_identity_by_exhaustive_enumeration(oracle, V, k, T, seed):
+    rng = np.random.default_rng(seed)
+    lp = rng.normal(0, 2, size=(k + 1, V)).astype(np.float32)
+    lq = (lp[:k] + rng.normal(0, 1.0, size=(k, V))).astype(np.float32)
+    p = np.stack([softmax64(r, T) for r in lp])
+    q = np.stack([softmax64(r, T) for r in lq])
+    # integration grid: every place where the outcome can change as a function of a uniform
+    acc_cells = []
+    for i in range(k):
+        acc_cells.append(_cells((p[i] / q[i])))
+    cdf_breaks = [np.cumsum(p[k])]                      # bonus distribution
+    for i in range(k):
+        r = np.maximum(p[i] - q[i], 0)
+        cdf_breaks.append(np.cumsum(r) / r.sum())
+    us_mid, us_wid = _cells(np.concatenate(cdf_breaks))
+    cases, weights = [], []
+    for xs in itertools.product(range(V), repeat=k):
+        wx = np.prod([q[i][xs[i]] for i in range(k)])
+        for ui in itertools.product(*[range(len(c[0])) for c in acc_cells]):
+            wu = np.prod([acc_cells[i][1][ui[i]] for i in range(k)])
+            u_acc = [acc_cells[i][0][ui[i]] for i in range(k)]
+            for m, w in zip(us_mid, us_wid):
+                cases.append((xs, u_acc, m))
+                weights.append(wx * wu * w)
+    weights = np.asarray(weights)
+    assert abs(weights.sum() - 1.0) < 1e-4
+    B = len(cases)
+    inp = _batch([lp] * B, [lq] * B, [c[0] for c in cases], [c[1] for c in cases],
+                 [c[2] for c in cases], [k] * B, T=T)
+    res = oracle.spec_accept(inp)
+    n, toks = res["accepted_len"], res["out_tokens"]
+    beta = [np.minimum(p[i], q[i]).sum() for i in range(k)]
+    reach = 1.0
+    for pos in range(k + 1):
+        got = np.zeros(V)
+        sel = n >= pos                      # a token is emitted at this position
+        np.add.at(got, toks[sel, pos], weights[sel])
+        # P(token at pos = y and pos reached) = prod_{i<pos} beta_i * p_pos(y)
+        assert np.max(np.abs(got - reach * p[pos])) < 2e-5, (pos, got, reach * p[pos])
+        if pos < k:
+            reach *= beta[pos]
+    # accepted-length law: P(n >= j) = prod_{i<j} beta_i
+    for j in range(1, k + 1):
+        assert abs(weights[n >= j].sum() - np.prod(beta[:j])) < 2e-5
+
+
+# ----------------------------------------------------------------------------- library sampling, special cases
+def test_depth_zero_is_inverse_cdf_sampling(oracle):
+    rng = np.random.default_rng(5)
+    B, V = 200, 97
+    lp = rng.normal(0, 2, size=(B, 1, V)).astype(np.float32)
+    us = rng.random(B).astype(np.float32)
+    T = 0.8
+    inp = _batch(list(lp), [np.zeros((0, V))] * B, [[]] * B, [[]] * B, us, [0] * B, T=T)
+    res = oracle.spec_accept(inp)
+    assert np.all(res["accepted_len"] == 0)
+    for b in range(B):
+        c = np.cumsum(softmax64(lp[b, 0], np.float32(T)))
+        y = int(np.searchsorted(c, np.float64(us[b]) * c[-1], side="right"))
+        assert res["out_tokens"][b, 0] == y and np.all(res["out_tokens"][b, 1:] == -1)
+        assert res["y_lo"][b] <= y <= res["y_hi"][b]
+    assert res["resid_sum"] == pytest.approx(np.ones(B), abs=1e-12)
+
+
+def test_identical_distributions_accept_everything(oracle):
+    rng = np.random.default_rng(6)
+    B, V, k = 50, 33, 4
+    lp = rng.normal(0, 2, size=(B, k + 1, V)).astype(np.float32)
+    toks = rng.integers(0, V, size=(B, k))
+    ua = rng.random((B, k)).astype(np.float32)
+    us = rng.random(B).astype(np.float32)
+    inp = _batch(list(lp), list(lp[:, :k]), list(toks), list(ua), us, [k] * B)
+    res = oracle.spec_accept(inp)
+    assert np.all(res["accepted_len"] == k)
+    assert np.array_equal(res["out_tokens"][:, :k], toks)
+    assert res["ratio"] == pytest.approx(np.ones(B * k), abs=1e-12)
+    for b in range(B):  # bonus token drawn from p_k
+        c = np.cumsum(softmax64(lp[b, k], 1.0))
+        assert res["out_tokens"][b, k] == int(np.searchsorted(c, np.float64(us[b]) * c[-1], side="right"))
+
+
+def test_impossible_draft_token_is_rejected_and_residual_is_target(oracle):
+    # draft puts all its mass on token a, target gives a zero mass: reject at 0, residual == p
+    rng = np.random.default_rng(7)
+    B, V, k, a = 40, 21, 3, 5
+    lp = rng.normal(0, 1.5, size=(B, k + 1, V)).astype(np.float32)
+    lp[:, :, a] = -1.0e4
+    lq = np.full((B, k, V), -1.0e4, np.float32)
+    lq[:, :, a] = 0.0
+    us = rng.random(B).astype(np.float32)
+    ua = np.zeros((B, k), np.float32)   # even u = 0 must not accept a zero-probability token
+    inp = _batch(list(lp), list(lq), [[a] * k] * B, list(ua), us, [k] * B)
+    res = oracle.spec_accept(inp)
+    assert np.all(res["accepted_len"] == 0)
+    assert res["resid_sum"] == pytest.approx(np.ones(B), abs=1e-12)
+    for b in range(B):
+        c = np.cumsum(softmax64(lp[b, 0], 1.0))
+        y = int(np.searchsorted(c, np.float64(us[b]) * c[-1], side="right"))
+        assert res["out_tokens"][b, 0] == y and y != a
+
+
+def test_zero_uniform_accepts_any_possible_token(oracle):
+    rng = np.random.default_rng(8)
+    B, V, k = 30, 17, 2
+    lp = rng.normal(0, 2, size=(B, k + 1, V)).astype(np.float32)
+    lq = rng.normal(0, 2, size=(B, k, V)).astype(np.float32)
+    toks = rng.integers(0, V, size=(B, k))
+    inp = _batch(list(lp), list(lq), list(toks), np.zeros((B, k)), rng.random(B), [k] * B)
+    res = oracle.spec_accept(inp)
+    assert np.all(res["accepted_len"] == k)
+
+
+def test_residual_mass_closed_form_and_ratio(oracle):
+    # sum_v max(0,p-q) = 1 - sum_v min(p,q); the reported ratio is p(x)/q(x)
+    cfg = TINY.scaled(batch=40, vocab=300, depth=("uniform", 1, 8), sigma_draft=("fixed", 1.5))
+    inp = synth.make_accept_inputs(cfg, seed=1)
+    res = oracle.spec_accept(inp)
+    tgt, drf = inp["target_logits"], inp["draft_logits"]
+    checked = 0
+    for b in range(inp["batch"]):
+        k, n = int(inp["depth"][b]), int(res["accepted_len"][b])
+        r0, d0 = inp["q_indptr"][b], inp["q_indptr"][b] - b
+        for i in range(k):
+            p, q = softmax64(tgt[r0 + i], 1.0), softmax64(drf[d0 + i], 1.0)
+            x = inp["draft_tokens"][d0 + i]
+            assert res["ratio"][d0 + i] == pytest.approx(p[x] / q[x], rel=1e-12)
+        if n < k:
+            p, q = softmax64(tgt[r0 + n], 1.0), softmax64(drf[d0 + n], 1.0)
+            assert res["resid_sum"][b] == pytest.approx(1.0 - np.minimum(p, q).sum(), abs=1e-12)
+            y = res["out_tokens"][b, n]
+            assert p[y] > q[y], "a resampled token must carry residual mass"
+            checked += 1
+        # the walk stops at the FIRST rejection, and everything before it was a real acceptance
+        flags = [np.float64(inp["u_accept"][d0 + i]) * softmax64(drf[d0 + i], 1.0)[inp["draft_tokens"][d0 + i]]
+                 < softmax64(tgt[r0 + i], 1.0)[inp["draft_tokens"][d0 + i]] for i in range(k)]
+        assert n == (flags.index(False) if False in flags else k)
+    assert checked > 5
+
+
+def test_accepted_length_law_monte_carlo(oracle):
+    # With x ~ q, P(n >= j) = prod_{i<j} sum_v min(p_i, q_i).  Compare the batch mean with its expectation.
+    cfg = TINY.scaled(batch=1500, vocab=64, depth=("fixed", 4), sigma_draft=("fixed", 0.8))
+    inp = synth.make_accept_inputs(cfg, seed=2)
+    res = oracle.spec_accept(inp)
+    tgt, drf = inp["target_logits"], inp["draft_logits"]
+    exp_n, var_n = 0.0, 0.0
+    for b in range(inp["batch"]):
+        r0, d0 = inp["q_indptr"][b], inp["q_indptr"][b] - b
+        surv, e, e2 = 1.0, 0.0, 0.0
+        probs = []
+        for i in range(4):
+            surv *= np.minimum(softmax64(tgt[r0 + i], 1.0), softmax64(drf[d0 + i], 1.0)).sum()
+            probs.append(surv)
+        e = sum(probs)                                        # E[n] = sum_j P(n >= j)
+        e2 = sum((2 * j + 1) * probs[j] for j in range(4))    # E[n^2] = sum_j (2j+1) P(n >= j+1)
+        exp_n += e
+        var_n += e2 - e * e
+    z = (res["accepted_len"].sum() - exp_n) / np.sqrt(var_n)
+    assert abs(z) < 4.5, z
+
+
+def test_out_tokens_layout_and_padding(oracle):
+    cfg = TINY.scaled(batch=32, vocab=128, depth=("uniform", 0, 8))
+    inp = synth.make_accept_inputs(cfg, seed=3)
+    res = oracle.spec_accept(inp)
+    for b in range(inp["batch"]):
+        n, d0 = int(res["accepted_len"][b]), inp["q_indptr"][b] - b
+        assert 0 <= n <= inp["depth"][b]
+        row = res["out_tokens"][b]
+        assert np.array_equal(row[:n], inp["draft_tokens"][d0:d0 + n])
+        assert 0 <= row[n] < 128 and np.all(row[n + 1:] == -1)
+        assert res["y_lo"][b] <= row[n] <= res["y_hi"][b]
+
+
+# ----------------------------------------------------------------------------- invariances
+def test_invariances(oracle):
+    cfg = TINY.scaled(batch=48, vocab=200, depth=("uniform", 0, 6), sigma_draft=("fixed", 1.0))
+    inp = synth.make_accept_inputs(cfg, seed=4)
+    base = oracle.spec_accept(inp)
+    # (logits, T) -> (2 logits, 2 T): exactly the same quotients, so bit-identical decisions
+    s = dict(inp)
+    s["target_logits"] = inp["target_logits"] * np.float32(2)
+    s["draft_logits"] = inp["draft_logits"] * np.float32(2)
+    s["temperature"] = inp["temperature"] * np.float32(2)
+    r = oracle.spec_accept(s)
+    assert np.array_equal(r["out_tokens"], base["out_tokens"])
+    # adding a constant to every logit of a row changes nothing (softmax shift invariance)
+    c = dict(inp)
+    c["target_logits"] = inp["target_logits"] + np.float32(8)
+    c["draft_logits"] = inp["draft_logits"] - np.float32(4)
+    r = oracle.spec_accept(c)
+    assert np.array_equal(r["accepted_len"], base["accepted_len"])
+    assert np.mean(r["out_tokens"] == base["out_tokens"]) > 0.99   # fp32 rounding of the shift may move a near-tie
+    # relabelling the vocabulary leaves the accepted lengths unchanged
+    perm = np.random.default_rng(0).permutation(200)
+    v = dict(inp)
+    v["target_logits"] = np.ascontiguousarray(inp["target_logits"][:, np.argsort(perm)])
+    v["draft_logits"] = np.ascontiguousarray(inp["draft_logits"][:, np.argsort(perm)])
+    v["draft_tokens"] = perm[inp["draft_tokens"]].astype(np.int32)
+    r = oracle.spec_accept(v)
+    assert np.array_equal(r["accepted_len"], base["accepted_len"])
+
+
+def test_per_request_temperature_and_row_stride(oracle):
+    cfg = TINY.scaled(batch=20, vocab=90, depth=("uniform", 0, 5))
+    a = synth.make_accept_inputs(cfg, seed=5)
+    b = synth.make_accept_inputs(cfg, seed=5, row_pad=7)   # padded rows hold a huge value that must be skipped
+    ra, rb = oracle.spec_accept(a), oracle.spec_accept(b)
+    assert np.array_equal(ra["out_tokens"], rb["out_tokens"])
+    # a request's result depends on its own temperature only
+    t = dict(a)
+    t["temperature"] = a["temperature"].copy()
+    t["temperature"][::2] = 0.5
+    rt = oracle.spec_accept(t)
+    assert np.array_equal(rt["out_tokens"][1::2], ra["out_tokens"][1::2])
+    solo = dict(a)
+    solo["temperature"] = np.full(20, 0.5, np.float32)
+    rs = oracle.spec_accept(solo)
+    assert np.array_equal(rt["out_tokens"][::2], rs["out_tokens"][::2])
+
+
+def test_near_tie_flags(oracle):
+    # u placed just beside p/q must be flagged, far away not
+    lp = np.array([[0.0, 0.0], [0.0, 0.0]], np.float32)          # p = (.5,.5)
+    lq = np.array([[np.log(3.0), 0.0]], np.float32)              # q = (.75,.25): p/q(token 0) = 2/3
+    rho = 0.5 / softmax64(lq[0], 1.0)[0]
+    us = [rho - 4e-6, rho + 4e-6, rho - 1e-3, rho + 1e-3]
+    inp = _batch([lp] * 4, [lq] * 4, [[0]] * 4, [[u] for u in us], [0.3] * 4, [1] * 4)
+    res = oracle.spec_accept(inp)
+    assert res["near_tie"].tolist() == [1, 1, 0, 0]
+    assert res["accepted_len"].tolist() == [1, 0, 1, 0]
+
+
+def test_bad_arguments_rejected(oracle):
+    cfg = TINY.scaled(batch=4, vocab=32)
+    inp = synth.make_accept_inputs(cfg, seed=0)
+    bad = dict(inp)
+    bad["temperature"] = np.zeros(4, np.float32)
+    with pytest.raises(ValueError):
+        oracle.spec_accept(bad)
+    bad = dict(inp)
+    bad["draft_tokens"] = inp["draft_tokens"].copy()
+    bad["draft_tokens"][0] = 32
+    with pytest.raises(ValueError):
+        oracle.spec_accept(bad)

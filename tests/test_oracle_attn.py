@@ -1,0 +1,268 @@
+"""Pins for the attention oracle: what the mathematics and library routines fix (CPU only).
+
+Each test is chosen so that a plausible mistake in oracle/spec_oracle.c (wrong
+causal offset, transposed operand, wrong head mapping, wrong scale index,
+missing normalisation, wrong block lookup) fails at least one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_09562_amd import synth
+from tests.helpers import gather_kv, q_values
+
+TINY = synth.CONFIGS[0]
+
+
+def _small(kv_dtype="f32", q_dtype="f32", **kw):
+    base = dict(batch=3, num_q_heads=8, num_kv_heads=2, head_dim=64, kv_dtype=kv_dtype, q_dtype=q_dtype,
+                ctx=("fixed", (37, 64, 131)), depth=("fixed", 3))
+    base.update(kw)
+    return TINY.scaled(**base)
+
+
+def _sdpa_reference(inp):
+    """torch's scaled_dot_product_attention in fp64 on gathered contiguous K/V, bottom-right aligned mask."""
+    R, Hq, D = inp["total_rows"], inp["num_q_heads"], inp["head_dim"]
+    G = Hq // inp["num_kv_heads"]
+    q = q_values(inp)
+    out = np.zeros((R, Hq, D))
+    for b in range(inp["batch"]):
+        r0, r1 = inp["q_indptr"][b], inp["q_indptr"][b + 1]
+        ql, L = r1 - r0, int(inp["kv_len"][b])
+        K = torch.from_numpy(gather_kv(inp, b, "k")).permute(1, 0, 2)  # [Hkv, L, D]
+        V = torch.from_numpy(gather_kv(inp, b, "v")).permute(1, 0, 2)
+        K = K.repeat_interleave(G, dim=0)  # consecutive query heads share one KV head
+        V = V.repeat_interleave(G, dim=0)
+        Q = torch.from_numpy(q[r0:r1]).permute(1, 0, 2)  # [Hq, ql, D]
+        mask = torch.zeros(ql, L, dtype=torch.bool)
+        for i in range(ql):
+            mask[i, : L - ql + i + 1] = True
+        o = torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=mask, scale=inp["sm_scale"])
+        out[r0:r1] = o.permute(1, 0, 2).numpy()
+    return out
+
+
+def test_decoders_match_torch_conversions(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.decode(bits, "bf16")
+    with np.errstate(invalid="ignore"):
+        ref = synth.decode_storage(bits, "bf16").astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok], ref[ok])
+    by = np.arange(256, dtype=np.uint8)
+    got = oracle.decode(by, "fp8")
+    ref = synth.decode_storage(by, "fp8").astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.isnan(got).sum() == 2
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok], ref[ok])
+    assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+
+
+@pytest.mark.parametrize("depth", [0, 1, 4, 8])
+@pytest.mark.parametrize("kv_dtype,q_dtype", [("f32", "f32"), ("bf16", "bf16"), ("fp8", "bf16")])
+def test_matches_library_attention(oracle, depth, kv_dtype, q_dtype):
+    # depth 0 is ordinary single-token decode attention over kv_len keys
+    cfg = _small(kv_dtype, q_dtype, depth=("fixed", depth))
+    inp = synth.make_attention_inputs(cfg, seed=depth)
+    out, lse = oracle.verify_attn(inp)
+    ref = _sdpa_reference(inp)
+    assert np.max(np.abs(out - ref)) < 1e-11
+    assert np.all(np.isfinite(lse))
+
+
+def test_ragged_depths_and_d128(oracle):
+    cfg = _small("bf16", "bf16", batch=5, num_q_heads=8, num_kv_heads=4, head_dim=128,
+                 ctx=("uniform", 20, 150), depth=("uniform", 0, 8))
+    inp = synth.make_attention_inputs(cfg, seed=3)
+    assert len(set(inp["depth"].tolist())) > 1
+    out, _ = oracle.verify_attn(inp)
+    assert np.max(np.abs(out - _sdpa_reference(inp))) < 1e-11
+
+
+def test_hand_worked_example(oracle):
+    # D=2, one head, three cached positions, one draft token (two query rows), sm_scale 1.
+    # Row 0 sees positions 0..1 with scores (1, 2); row 1 sees 0..2 with scores (.5, -1, -.5).
+    K = np.array([[1, 0], [0, 1], [1, 1]], dtype=np.float32)
+    V = np.array([[1, 2], [3, 4], [5, 6]], dtype=np.float32)
+    Q = np.array([[1, 2], [0.5, -1]], dtype=np.float32)
+    kc = np.full((2, 1, 16, 2), np.nan, dtype=np.float32)
+    vc = np.full((2, 1, 16, 2), np.nan, dtype=np.float32)
+    kc[1, 0, :3] = K
+    vc[1, 0, :3] = V
+    inp = dict(batch=1, num_q_heads=1, num_kv_heads=1, head_dim=2, block_size=16, num_blocks=2,
+               max_blocks_per_seq=1, total_rows=2, kv_dtype="f32", q_dtype="f32",
+               kv_len=np.array([3], np.int32), q_indptr=np.array([0, 2], np.int32),
+               block_table=np.array([[1]], np.int32), k_cache=kc, v_cache=vc, k_scale=None, v_scale=None,
+               q=Q.reshape(2, 1, 2), sm_scale=1.0)
+    out, lse = oracle.verify_attn(inp)
+    e = math.e
+    assert out[0, 0] == pytest.approx([(1 + 3 * e) / (1 + e), (2 + 4 * e) / (1 + e)], abs=1e-14)
+    assert lse[0, 0] == pytest.approx(1 + math.log(1 + e), abs=1e-14)
+    w = np.exp([0.5, -1.0, -0.5])
+    assert out[1, 0] == pytest.approx((w @ V.astype(np.float64)) / w.sum(), abs=1e-14)
+    assert lse[1, 0] == pytest.approx(math.log(w.sum()), abs=1e-14)
+
+
+def test_prefix_consistency(oracle):
+    # Row i of a depth-k verify equals plain decode (depth 0) on the cache cut at that row's position.
+    cfg = _small("bf16", "bf16", depth=("fixed", 5))
+    inp = synth.make_attention_inputs(cfg, seed=1)
+    out, lse = oracle.verify_attn(inp)
+    B = inp["batch"]
+    for i in range(6):
+        cut = dict(inp)
+        cut["kv_len"] = (inp["kv_len"] - 5 + i).astype(np.int32)
+        cut["q_indptr"] = np.arange(B + 1, dtype=np.int32)
+        cut["total_rows"] = B
+        cut["q"] = np.ascontiguousarray(inp["q"][inp["q_indptr"][:-1] + i])
+        o1, l1 = oracle.verify_attn(cut)
+        rows = inp["q_indptr"][:-1] + i
+        assert np.max(np.abs(o1 - out[rows])) < 1e-13
+        assert np.max(np.abs(l1 - lse[rows])) < 1e-13
+
+
+@pytest.mark.parametrize("part", [16, 48, 1000])
+def test_split_and_merge_equals_unsplit(oracle, part):
+    cfg = _small("fp8", "bf16")
+    inp = synth.make_attention_inputs(cfg, seed=2)
+    o0, l0 = oracle.verify_attn(inp)
+    o1, l1 = oracle.verify_attn(inp, part_tokens=part)
+    assert np.max(np.abs(o0 - o1)) < 1e-12
+    assert np.max(np.abs(l0 - l1)) < 1e-12
+
+
+def test_lse_is_log_of_summed_exponentials(oracle):
+    cfg = _small("f32", "f32", batch=1, ctx=("fixed", (45,)), depth=("fixed", 2))
+    inp = synth.make_attention_inputs(cfg, seed=7)
+    _, lse = oracle.verify_attn(inp)
+    K = gather_kv(inp, 0, "k")
+    q = q_values(inp)
+    for i in range(3):
+        vis = 45 - 3 + i + 1
+        for h in range(8):
+            s = inp["sm_scale"] * (K[:vis, h // 4] @ q[i, h])
+            assert lse[i, h] == pytest.approx(math.log(np.exp(s).sum()), abs=1e-12)
+
+
+def test_closed_forms(oracle):
+    cfg = _small("f32", "f32")
+    inp = synth.make_attention_inputs(cfg, seed=4)
+    D = inp["head_dim"]
+    # (a) every value row equal to one vector: the output is that vector (weights sum to one)
+    a = dict(inp)
+    vec = np.linspace(-1, 1, D).astype(np.float32)
+    a["v_cache"] = np.broadcast_to(vec, inp["v_cache"].shape).copy()
+    out, _ = oracle.verify_attn(a)
+    assert np.max(np.abs(out - vec.astype(np.float64))) < 1e-12
+    # (b) every key row equal / (c) zero queries: uniform weights, output = mean of the visible values
+    for variant in ("k_const", "q_zero"):
+        c = dict(inp)
+        if variant == "k_const":
+            c["k_cache"] = np.broadcast_to(vec, inp["k_cache"].shape).copy()
+        else:
+            c["q"] = np.zeros_like(inp["q"])
+        out, lse = oracle.verify_attn(c)
+        for b in range(inp["batch"]):
+            V = gather_kv(inp, b, "v")
+            L, r0 = int(inp["kv_len"][b]), inp["q_indptr"][b]
+            ql = inp["q_indptr"][b + 1] - r0
+            for i in range(ql):
+                vis = L - ql + i + 1
+                for h in range(inp["num_q_heads"]):
+                    assert np.max(np.abs(out[r0 + i, h] - V[:vis, h // 4].mean(0))) < 1e-12
+                    if variant == "q_zero":
+                        assert lse[r0 + i, h] == pytest.approx(math.log(vis), abs=1e-12)
+
+
+def test_block_permutation_invariance(oracle):
+    cfg = _small("bf16", "bf16")
+    inp = synth.make_attention_inputs(cfg, seed=5)
+    o0, l0 = oracle.verify_attn(inp)
+    rng = np.random.default_rng(0)
+    perm = rng.permutation(inp["num_blocks"])          # new id of old block j is perm[j]
+    moved = dict(inp)
+    for name in ("k_cache", "v_cache"):
+        x = np.empty_like(inp[name])
+        x[perm] = inp[name]
+        moved[name] = x
+    bt = inp["block_table"].copy()
+    bt[bt >= 0] = perm[bt[bt >= 0]]
+    moved["block_table"] = bt.astype(np.int32)
+    o1, l1 = oracle.verify_attn(moved)
+    assert np.array_equal(o0, o1) and np.array_equal(l0, l1)
+
+
+def test_gqa_head_mapping(oracle):
+    cfg = _small("f32", "f32")
+    inp = synth.make_attention_inputs(cfg, seed=6)
+    q = inp["q"].copy()
+    q[:, 1] = q[:, 0]   # heads 0 and 1 share KV head 0 -> identical outputs
+    q[:, 4] = q[:, 0]   # head 4 uses KV head 1 -> different output
+    inp["q"] = q
+    out, _ = oracle.verify_attn(inp)
+    assert np.array_equal(out[:, 0], out[:, 1])
+    assert np.max(np.abs(out[:, 0] - out[:, 4])) > 1e-3
+
+
+def test_fp8_equals_f32_on_dequantised_cache(oracle):
+    # With power-of-two scales the dequantised cache is exactly representable in fp32, so the
+    # fp8 path must agree with the fp32 path run on it: pins the byte format and the scale indexing.
+    cfg = _small("fp8", "bf16")
+    inp = synth.make_attention_inputs(cfg, seed=8)
+    rng = np.random.default_rng(1)
+    for sc in ("k_scale", "v_scale"):
+        inp[sc] = (2.0 ** rng.integers(-6, -2, size=inp[sc].shape)).astype(np.float32)
+    o8, l8 = oracle.verify_attn(inp)
+    deq = dict(inp)
+    for name, sc in (("k_cache", "k_scale"), ("v_cache", "v_scale")):
+        x = synth.decode_storage(inp[name], "fp8") * inp[sc][:, :, None, None]
+        deq[name] = np.ascontiguousarray(x, dtype=np.float32)
+    deq["kv_dtype"] = "f32"
+    deq["k_scale"] = deq["v_scale"] = None
+    o32, l32 = oracle.verify_attn(deq)
+    assert np.max(np.abs(o8 - o32)) < 1e-12 and np.max(np.abs(l8 - l32)) < 1e-12
+    # the scale arrays must matter (guards against an ignored or mis-indexed scale)
+    z = dict(inp)
+    z["v_scale"] = np.ones_like(inp["v_scale"])
+    oz, _ = oracle.verify_attn(z)
+    assert np.max(np.abs(oz - o8)) > 1e-2
+
+
+def test_large_scores_stay_finite(oracle):
+    cfg = _small("f32", "f32")
+    inp = synth.make_attention_inputs(cfg, seed=9)
+    inp["q"] = (inp["q"] * 30).astype(np.float32)
+    out, lse = oracle.verify_attn(inp)
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+    assert np.max(np.abs(out - _sdpa_reference(inp))) < 1e-10
+
+
+def test_tail_garbage_and_unreferenced_blocks_are_ignored(oracle):
+    cfg = _small("bf16", "bf16")
+    a = synth.make_attention_inputs(cfg, seed=10)
+    b = synth.make_attention_inputs(cfg, seed=10, nan_tail=True)
+    oa, _ = oracle.verify_attn(a)
+    ob, _ = oracle.verify_attn(b)
+    assert np.array_equal(oa, ob) and np.all(np.isfinite(oa))
+
+
+def test_request_subset(oracle):
+    cfg = _small("bf16", "bf16")
+    inp = synth.make_attention_inputs(cfg, seed=11)
+    full, _ = oracle.verify_attn(inp)
+    sub, _ = oracle.verify_attn(inp, requests=[2])
+    r0, r1 = inp["q_indptr"][2], inp["q_indptr"][3]
+    assert np.array_equal(sub[r0:r1], full[r0:r1]) and np.all(np.isnan(sub[:r0]))
+
+
+def test_bad_arguments_rejected(oracle):
+    cfg = _small("f32", "f32")
+    inp = synth.make_attention_inputs(cfg, seed=0)
+    bad = dict(inp)
+    bad["kv_len"] = np.array([2, 64, 131], np.int32)  # shorter than its own query rows
+    with pytest.raises(ValueError):
+        oracle.verify_attn(bad)
