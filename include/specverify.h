@@ -1,0 +1,190 @@
+/*
+ * specverify: the decode lane's speculative-verification step on one MI355X.
+ *
+ * Two operations, both defined by the method the paper builds on (Section 2.2:
+ * draft tokens are verified by the target model in one parallel pass while the
+ * target's output distribution is preserved), with the per-request draft depth
+ * k chosen by the paper's controller (Section 3.5, Alg. 4, Eq. 13) and handed
+ * in as a ragged row count:
+ *
+ *   ss_spec_verify_attn  attention of each request's k+1 new tokens (causal
+ *                        among themselves) over its paged KV cache
+ *                        (Section 2.4; the cache holds prefill KV with decoded
+ *                        tokens appended, Section 3.4 Eq. 7)
+ *   ss_spec_accept       accept/reject walk over the k drafts and the draw of
+ *                        the one new token (residual or bonus distribution)
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory on the current device, "host"
+ *     pointers ordinary host memory.  The caller owns every buffer, including
+ *     the workspace; the library allocates no device memory, frees nothing and
+ *     keeps no state between calls (except the optional profiling events).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.
+ *   - Return value: SS_OK or an ss_status error; ss_last_error() gives the
+ *     thread's last message.  Host-visible arguments are validated before
+ *     anything is launched; on error nothing has been enqueued.  Contents of
+ *     device arrays (block ids inside the pool, kv_len >= q_len, draft tokens
+ *     inside the vocabulary) are the caller's responsibility.
+ *   - There is no CPU fallback: without a usable GPU the calls fail with
+ *     SS_ERR_DEVICE.
+ */
+#ifndef SPECVERIFY_H
+#define SPECVERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SS_OK = 0,
+    SS_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad dtype, misaligned buffer */
+    SS_ERR_UNSUPPORTED = 2, /* valid, but no kernel is built for this combination */
+    SS_ERR_WORKSPACE = 3,   /* workspace smaller than the *_workspace() query */
+    SS_ERR_DEVICE = 4       /* HIP reported an error (message has the HIP text) */
+} ss_status;
+
+typedef enum {
+    SS_F32 = 0,
+    SS_BF16 = 1,     /* bfloat16: upper 16 bits of an IEEE float32 */
+    SS_FP8_E4M3 = 2  /* OCP e4m3fn byte (bias 7, max 448, no inf, NaN = S.1111.111); KV cache only */
+} ss_dtype;
+
+#define SS_BLOCK_SIZE 16 /* tokens per KV block */
+#define SS_MAX_DEPTH 8   /* largest k; a request brings 1..9 query rows */
+#define SS_OUT_WIDTH 9   /* out_tokens row width = SS_MAX_DEPTH + 1 */
+
+/*
+ * Paged KV cache of one layer (Section 2.4).
+ *   k, v     device, dense [num_blocks][num_kv_heads][block_size][head_dim] in `dtype`,
+ *            16-byte aligned.  Slots past a request's kv_len and blocks no request
+ *            references may hold anything (NaN included); they are never used.
+ *   k_scale, v_scale  device float [num_blocks][num_kv_heads]; required iff dtype is
+ *            SS_FP8_E4M3 (value = decode(byte) * scale), must be NULL otherwise.
+ */
+typedef struct ss_paged_kv {
+    int32_t num_blocks;
+    int32_t block_size; /* must be SS_BLOCK_SIZE */
+    int32_t num_kv_heads;
+    int32_t head_dim;   /* 64 or 128 */
+    int32_t dtype;      /* ss_dtype */
+    const void *k;
+    const void *v;
+    const float *k_scale;
+    const float *v_scale;
+} ss_paged_kv;
+
+/*
+ * One decode-lane batch.
+ *   block_table  device int32 [batch][max_blocks_per_seq]: logical block j of request b
+ *                is physical block block_table[b][j]; entries past ceil(kv_len/16) are ignored.
+ *   kv_len       device int32 [batch]: valid cache positions of each request, INCLUDING the
+ *                q_len new tokens of this step, whose K/V the caller has already appended.
+ *   q_indptr     device int32 [batch+1]: request b owns query rows q_indptr[b]..q_indptr[b+1]-1
+ *                (q_len = k_b + 1 in 1..9, row i = the i-th new token, at position kv_len-q_len+i).
+ *   max_q_len    host value: an upper bound of q_len over the batch (the controller's largest depth
+ *                this step, plus one), or 0 if unknown (9 is assumed).  A tight bound lets the
+ *                library pick a kernel with fewer padded query rows; a bound that some request
+ *                exceeds is a caller error (rows beyond it are not computed).
+ */
+typedef struct ss_batch {
+    int32_t batch;
+    int32_t max_blocks_per_seq;
+    int32_t max_q_len;
+    int32_t reserved; /* must be 0 */
+    const int32_t *block_table;
+    const int32_t *kv_len;
+    const int32_t *q_indptr;
+} ss_batch;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t ss_version(void);
+
+/* Message of the calling thread's most recent failing call ("" if none). Never NULL. */
+const char *ss_last_error(void);
+
+/*
+ * Bytes of device workspace ss_spec_verify_attn needs for this shape (256-byte aligned
+ * buffer).  Depends only on the host-visible fields, not on device contents.  Returns 0 and
+ * sets the error message if the arguments are invalid.
+ */
+size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batch, int32_t num_q_heads,
+                                     int32_t total_rows);
+
+/*
+ * Verify attention (Section 2.2 "parallel verification", over the cache of Sections 2.4/3.4).
+ * For request b, new token i, query head h (KV head h / (num_q_heads/num_kv_heads)):
+ *     s_t = sm_scale * <q[row,h,:], K_b[t,:]>   for cache positions t = 0 .. kv_len_b - q_len_b + i
+ *     out[row,h,:] = sum_t softmax(s)_t * V_b[t,:],      lse[row,h] = ln sum_t exp(s_t)
+ *
+ *   q      device [total_rows][num_q_heads][head_dim], q_dtype SS_F32 or SS_BF16, 16-byte aligned
+ *   out    device, same shape and dtype as q (rounded to nearest even from fp32 accumulators)
+ *   lse    device float [total_rows][num_q_heads], or NULL
+ *   total_rows  must equal q_indptr[batch] (host copy of that value)
+ *   workspace   device, >= ss_spec_verify_attn_workspace(...) bytes; contents are scratch
+ *
+ * Internally the KV stream is cut into partitions that are reduced independently and merged
+ * by their log-sum-exp; the result does not depend on the partitioning beyond fp32 rounding.
+ * batch == 0 or total_rows == 0 is a no-op returning SS_OK.
+ */
+int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,
+                            int32_t num_q_heads, int32_t total_rows, float sm_scale, void *out, float *lse,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace ss_spec_accept needs (0 + error message on invalid arguments). */
+size_t ss_spec_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab);
+
+/*
+ * Acceptance walk and resampling (the speculative-sampling rule behind Section 2.2's
+ * "preserving output distribution").  Request b has k = q_len-1 drafts x_0..x_{k-1}; its
+ * target rows are rows q_indptr[b].. of target_logits (row i judges draft i, row k is the
+ * bonus distribution); its draft rows / tokens / u_accept entries start at q_indptr[b]-b.
+ *
+ *     p_i = softmax(target_i / T_b),  q_i = softmax(draft_i / T_b)
+ *     accept draft i iff u_accept_i < p_i[x_i] / q_i[x_i]; n = index of the first rejection (k if none)
+ *     r = max(0, p_n - q_n) if n < k, else p_k;  y = first token whose running sum of r (token
+ *     order) exceeds u_sample_b * sum(r)
+ *     out_tokens[b] = x_0..x_{n-1}, y, then -1 up to SS_OUT_WIDTH;  accepted_len[b] = n
+ *   greedy != 0: accept while the lowest-index argmax of target_i equals x_i; y = that argmax of
+ *   target_n; temperatures and uniforms are not read (their pointers may be NULL).
+ *
+ *   vocab, row_stride   logits rows hold `vocab` entries, `row_stride` elements apart (>= vocab)
+ *   logit_dtype         SS_F32 or SS_BF16; rows must start 16-byte aligned
+ *   total_rows          host copy of q_indptr[batch]; the draft-side arrays have total_rows-batch entries
+ *   temperature         device float [batch] (> 0), or NULL to use temperature_scalar for all
+ *   ratio_out           device float [total_rows-batch] or NULL: p/q of every draft (diagnostic)
+ *   Row statistics are accumulated in fp32/fp64; the resampling pass runs in fp64 so that the
+ *   drawn token is reproducible against an fp64 reference.
+ */
+int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
+                       const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                       const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                       const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
+                       int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Options (process-wide, not thread-safe; meant for tests and measurement).
+ *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
+ *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic
+ * Returns SS_ERR_INVALID_ARG for an unknown name or value.
+ */
+int32_t ss_set_option(const char *name, int64_t value);
+
+/*
+ * Kernel timing for the benchmark.  After ss_profile_begin(n) the next n calls of
+ * ss_spec_verify_attn record a HIP event pair around their KV-streaming kernel (the dominant
+ * one) on the caller's stream.  ss_profile_collect synchronises on those events, writes up to
+ * `cap` durations in milliseconds to the host array `ms`, returns how many were written and
+ * ends profiling.  Events are the only objects the library creates; they are destroyed here.
+ */
+int32_t ss_profile_begin(int32_t max_calls);
+int32_t ss_profile_collect(float *ms, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVERIFY_H */

@@ -1,0 +1,249 @@
+// C-ABI entry points: argument validation, workspace sizing, dispatch.  No arithmetic here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace ss {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t hip_fail(hipError_t e, const char *what)
+{
+    return fail(SS_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// process-wide options and profiling state
+static int64_t g_attn_path = 0;
+static int64_t g_attn_waves = 0;
+static std::vector<hipEvent_t> g_events;  // pairs
+static int g_prof_cap = 0, g_prof_used = 0;
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int32_t check_attn_shape(const ss_paged_kv *kv, const ss_batch *b, int32_t num_q_heads, int32_t total_rows)
+{
+    if (!kv || !b) return fail(SS_ERR_INVALID_ARG, "kv and batch descriptors must not be NULL");
+    if (kv->block_size != SS_BLOCK_SIZE)
+        return fail(SS_ERR_INVALID_ARG, "block_size must be %d, got %d", SS_BLOCK_SIZE, kv->block_size);
+    if (kv->head_dim != 64 && kv->head_dim != 128)
+        return fail(SS_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", kv->head_dim);
+    if (kv->num_kv_heads <= 0 || num_q_heads <= 0 || num_q_heads % kv->num_kv_heads)
+        return fail(SS_ERR_INVALID_ARG, "num_q_heads (%d) must be a positive multiple of num_kv_heads (%d)",
+                    num_q_heads, kv->num_kv_heads);
+    if (num_q_heads / kv->num_kv_heads > 16)
+        return fail(SS_ERR_UNSUPPORTED, "more than 16 query heads per KV head is not built");
+    if (kv->dtype < SS_F32 || kv->dtype > SS_FP8_E4M3)
+        return fail(SS_ERR_INVALID_ARG, "unknown KV dtype %d", kv->dtype);
+    if (b->batch < 0 || total_rows < 0) return fail(SS_ERR_INVALID_ARG, "negative batch or total_rows");
+    if (total_rows < b->batch || (int64_t)total_rows > (int64_t)b->batch * SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "total_rows (%d) must lie in [batch, %d*batch] for batch %d", total_rows,
+                    SS_OUT_WIDTH, b->batch);
+    if (b->batch > 0 && b->max_blocks_per_seq <= 0)
+        return fail(SS_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
+    if (kv->num_blocks < 0) return fail(SS_ERR_INVALID_ARG, "negative num_blocks");
+    if (b->max_q_len < 0 || b->max_q_len > SS_OUT_WIDTH || b->reserved != 0)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d], reserved must be 0", SS_OUT_WIDTH);
+    return SS_OK;
+}
+
+int attn_default_waves()
+{
+    if (g_attn_waves > 0) return (int)g_attn_waves;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    } else {
+        (void)hipGetLastError();
+    }
+    return cus * 8;  // two 4-wave workgroups per compute unit
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" {
+
+int32_t ss_version(void) { return 100; }
+
+const char *ss_last_error(void) { return g_err; }
+
+int32_t ss_set_option(const char *name, int64_t value)
+{
+    if (!name) return fail(SS_ERR_INVALID_ARG, "option name is NULL");
+    if (!strcmp(name, "attn_path")) {
+        if (value < 0 || value > 2) return fail(SS_ERR_INVALID_ARG, "attn_path must be 0, 1 or 2");
+        g_attn_path = value;
+        return SS_OK;
+    }
+    if (!strcmp(name, "attn_waves")) {
+        if (value < 0 || value > 65536 || value % kWavesPerWg)
+            return fail(SS_ERR_INVALID_ARG, "attn_waves must be a multiple of %d in [0, 65536]", kWavesPerWg);
+        g_attn_waves = value;
+        return SS_OK;
+    }
+    return fail(SS_ERR_INVALID_ARG, "unknown option '%s'", name);
+}
+
+size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batch, int32_t num_q_heads,
+                                     int32_t total_rows)
+{
+    if (check_attn_shape(kv, batch, num_q_heads, total_rows) != SS_OK) return 0;
+    return attn_workspace_bytes(batch->batch, num_q_heads, kv->num_kv_heads, kv->head_dim, attn_default_waves());
+}
+
+int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,
+                            int32_t num_q_heads, int32_t total_rows, float sm_scale, void *out, float *lse,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_attn_shape(kv, batch, num_q_heads, total_rows);
+    if (rc != SS_OK) return rc;
+    if (batch->batch == 0 || total_rows == 0) return SS_OK;
+    if (q_dtype != SS_F32 && q_dtype != SS_BF16) return fail(SS_ERR_INVALID_ARG, "q_dtype must be SS_F32 or SS_BF16");
+    if (!kv->k || !kv->v || !batch->block_table || !batch->kv_len || !batch->q_indptr || !q || !out)
+        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if ((kv->dtype == SS_FP8_E4M3) != (kv->k_scale != nullptr) || (kv->k_scale == nullptr) != (kv->v_scale == nullptr))
+        return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
+    if (!aligned16(kv->k) || !aligned16(kv->v) || !aligned16(q) || !aligned16(out))
+        return fail(SS_ERR_INVALID_ARG, "k, v, q and out must be 16-byte aligned");
+    if (!(sm_scale == sm_scale) || sm_scale <= 0.0f) return fail(SS_ERR_INVALID_ARG, "sm_scale must be positive");
+    const int launch_waves = attn_default_waves();
+    const size_t need = attn_workspace_bytes(batch->batch, num_q_heads, kv->num_kv_heads, kv->head_dim, launch_waves);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
+    if (workspace_bytes < need)
+        return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+
+    AttnArgs a{};
+    a.k = kv->k; a.v = kv->v; a.k_scale = kv->k_scale; a.v_scale = kv->v_scale;
+    a.num_kv_heads = kv->num_kv_heads; a.head_dim = kv->head_dim; a.kv_dtype = kv->dtype;
+    a.batch = batch->batch; a.max_blocks = batch->max_blocks_per_seq;
+    a.block_table = batch->block_table; a.kv_len = batch->kv_len; a.q_indptr = batch->q_indptr;
+    a.q = q; a.out = out; a.lse = lse; a.q_dtype = q_dtype; a.num_q_heads = num_q_heads; a.total_rows = total_rows;
+    a.sm_scale = sm_scale;
+    a.launch_waves = launch_waves;
+    const int G = num_q_heads / kv->num_kv_heads;
+    a.rows_pad = (int)align_up((size_t)SS_OUT_WIDTH * G, 16);
+    a.max_q_len = batch->max_q_len ? batch->max_q_len : SS_OUT_WIDTH;
+    // carve the workspace
+    char *w = static_cast<char *>(workspace);
+    a.plan = reinterpret_cast<AttnPlan *>(w);
+    w += 256;
+    a.tile_prefix = reinterpret_cast<int32_t *>(w);
+    w += align_up(sizeof(int32_t) * ((size_t)batch->batch + 1), 256);
+    const size_t slots = (size_t)launch_waves + (size_t)batch->batch * kv->num_kv_heads;
+    a.part_ml = reinterpret_cast<float *>(w);
+    w += align_up(slots * a.rows_pad * 2 * sizeof(float), 256);
+    a.part_o = reinterpret_cast<float *>(w);
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (g_prof_used < g_prof_cap) {
+        ev0 = g_events[2 * g_prof_used];
+        ev1 = g_events[2 * g_prof_used + 1];
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mfma_ok = attn_mfma_supported(a);
+    if (g_attn_path == 2 && !mfma_ok)
+        return fail(SS_ERR_UNSUPPORTED, "attn_path=2 but the MFMA kernel does not cover this shape/dtype");
+    if (mfma_ok && g_attn_path != 1)
+        rc = attn_mfma_launch(a, s, ev0, ev1);
+    else
+        rc = attn_generic_launch(a, s, ev0, ev1);
+    if (rc == SS_OK && ev0) ++g_prof_used;
+    return rc;
+}
+
+size_t ss_spec_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab)
+{
+    if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH) {
+        fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
+        return 0;
+    }
+    return accept_workspace_bytes(batch, total_rows, vocab);
+}
+
+int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
+                       const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                       const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                       const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
+                       int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
+    if (batch == 0) return SS_OK;
+    if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
+    if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
+        return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
+    const int64_t esz = logit_dtype == SS_F32 ? 4 : 2;
+    const int n_draft = total_rows - batch;
+    if (!q_indptr || !target_logits || !accepted_len || !out_tokens)
+        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (n_draft > 0 && (!draft_tokens || (!greedy && (!draft_logits || !u_accept))))
+        return fail(SS_ERR_INVALID_ARG, "draft-side arrays must be given when any request has drafts");
+    if (!greedy && !u_sample) return fail(SS_ERR_INVALID_ARG, "u_sample is required unless greedy");
+    if (!greedy && !temperature && !(temperature_scalar > 0.0f))
+        return fail(SS_ERR_INVALID_ARG, "temperature must be positive unless greedy");
+    if (!aligned16(target_logits) || (draft_logits && !aligned16(draft_logits)) || (row_stride * esz) % 16)
+        return fail(SS_ERR_INVALID_ARG, "logits rows must start 16-byte aligned (base and row_stride)");
+    const size_t need = accept_workspace_bytes(batch, total_rows, vocab);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
+    if (workspace_bytes < need)
+        return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    AcceptArgs a{};
+    a.batch = batch; a.vocab = vocab; a.logit_dtype = logit_dtype; a.total_rows = total_rows; a.greedy = greedy ? 1 : 0;
+    a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft = draft_logits;
+    a.draft_tokens = draft_tokens; a.u_accept = u_accept; a.u_sample = u_sample; a.temperature = temperature;
+    a.temperature_scalar = temperature_scalar; a.accepted_len = accepted_len; a.out_tokens = out_tokens;
+    a.ratio_out = ratio_out; a.workspace = workspace;
+    return accept_launch(a, static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_profile_begin(int32_t max_calls)
+{
+    if (max_calls < 0 || max_calls > 100000) return fail(SS_ERR_INVALID_ARG, "max_calls out of range");
+    for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
+    g_events.clear();
+    g_prof_cap = g_prof_used = 0;
+    for (int i = 0; i < 2 * max_calls; ++i) {
+        hipEvent_t e;
+        SS_HIP_CHECK(hipEventCreate(&e), "hipEventCreate");
+        g_events.push_back(e);
+    }
+    g_prof_cap = max_calls;
+    return SS_OK;
+}
+
+int32_t ss_profile_collect(float *ms, int32_t cap)
+{
+    int n = 0;
+    for (int i = 0; i < g_prof_used; ++i) {
+        float t = 0.f;
+        if (hipEventSynchronize(g_events[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&t, g_events[2 * i], g_events[2 * i + 1]) != hipSuccess) {
+            (void)hipGetLastError();
+            break;
+        }
+        if (ms && n < cap) ms[n++] = t;
+    }
+    for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
+    g_events.clear();
+    g_prof_cap = g_prof_used = 0;
+    return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,502 @@
+// Verify attention on the matrix cores (gfx950), head_dim 128, bf16 queries, bf16 or e4m3 cache.
+//
+// Work decomposition.  The KV cache of one (request, KV head) pair ("unit") is a run of
+// 16-token tiles, one per cache block.  All tiles of all units form one flat sequence (unit
+// major); it is cut into `num_waves` equal contiguous spans and every wavefront streams one
+// span, so the load is balanced whatever the mix of context lengths.  A span may cover the
+// tail of one unit, several whole units and the head of another; for every unit it touches
+// the wave emits one partial result (running max, sum, unnormalised output) into slot
+// `wave + unit` (that sum is unique along the sequence).  A second kernel merges the partials
+// of each unit by their log-sum-exp and writes the rounded output.
+//
+// Per tile, with rows = (k+1) * (query heads per KV head) padded to a multiple of 16:
+//   S^T[token][row] = K[token][:] . Q[row][:]   v_mfma_f32_16x16x32_bf16, K tile as A operand
+//   online softmax on S^T in registers (a row's 16 scores sit in 4 lanes x 4 registers)
+//   O^T[d][row]    += V[token][d] * P[row][token]   v_mfma_f32_16x16x16_bf16, P taken straight
+//                     from the S^T accumulator layout, V as A operand
+// Both K and V are read from HBM directly in operand layout with 16-byte loads: for K a lane
+// holds 8 consecutive d of one token; for V a lane holds d = 8*i .. 8*i+7 of four tokens and
+// the eight M-blocks of O^T are the eight interleaved d-phases, so no transpose through LDS is
+// needed (only a 16-bit pack per operand register).
+#include <type_traits>
+
+#include "common.h"
+
+namespace ss {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+constexpr int D = 128;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---------------------------------------------------------------------------------------------
+// plan: tile prefix over requests, total tiles, number of partitions
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
+{
+    __shared__ int wsum[4];
+    __shared__ int carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < a.batch; base += 256) {
+        const int b = base + tid;
+        const int n = b < a.batch ? (a.kv_len[b] + kTile - 1) / kTile : 0;
+        int incl = n;  // inclusive scan inside the wave
+        for (int off = 1; off < 64; off <<= 1) {
+            int t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        int before = carry_s;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        if (b < a.batch) a.tile_prefix[b] = before + incl - n;
+        __syncthreads();
+        if (tid == 255) carry_s = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const int per_head = carry_s;
+        a.tile_prefix[a.batch] = per_head;
+        const long long total = (long long)per_head * a.num_kv_heads;
+        long long nw = total / kMinTilesPerWave;
+        if (nw < 1) nw = 1;
+        if (nw > a.launch_waves) nw = a.launch_waves;
+        a.plan->total_tiles = (int)total;
+        a.plan->num_waves = (int)nw;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// streaming kernel
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t lo_src, uint32_t hi_src)
+{
+    // (hi_src & 0xffff0000) | (lo_src >> 16): upper halves of two words
+    return __builtin_amdgcn_perm(hi_src, lo_src, 0x07060302u);
+}
+__device__ __forceinline__ uint32_t pack_lo16(uint32_t lo_src, uint32_t hi_src)
+{
+    return __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);
+}
+
+// 8 e4m3 bytes (two words) -> 8 bf16 (exact: e4m3 has 4 significant bits)
+__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1)
+{
+    const float2v a = __builtin_amdgcn_cvt_pk_f32_fp8(w0, false);
+    const float2v b = __builtin_amdgcn_cvt_pk_f32_fp8(w0, true);
+    const float2v c = __builtin_amdgcn_cvt_pk_f32_fp8(w1, false);
+    const float2v d = __builtin_amdgcn_cvt_pk_f32_fp8(w1, true);
+    uint4 r;
+    r.x = pack_hi16(__float_as_uint(a.x), __float_as_uint(a.y));
+    r.y = pack_hi16(__float_as_uint(b.x), __float_as_uint(b.y));
+    r.z = pack_hi16(__float_as_uint(c.x), __float_as_uint(c.y));
+    r.w = pack_hi16(__float_as_uint(d.x), __float_as_uint(d.y));
+    return r;
+}
+
+template <bool FP8>
+struct TileRegs {
+    // bf16: k[ks] = 8 bf16 of token (lane&15) at d = 32*ks + 8*(lane>>4)
+    // fp8 : k[kk] = 16 bytes of token (lane&15) at d = 64*kk + 16*(lane>>4)   (kk = 0,1)
+    uint4 k[FP8 ? 2 : 4];
+    // bf16: v[e] = 8 bf16 of token 4*(lane>>4)+e at d = 8*(lane&15)
+    // fp8 : v[e] = 8 bytes of the same
+    typename std::conditional<FP8, uint2, uint4>::type v[4];
+    float ks, vs;  // block scales (fp8), 1 otherwise
+};
+
+template <bool FP8>
+__device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, int64_t phys, int g, int lane)
+{
+    constexpr int ES = FP8 ? 1 : 2;
+    const int64_t blk = (phys * a.num_kv_heads + g) * (int64_t)(kTile * D * ES);
+    const char *kp = static_cast<const char *>(a.k) + blk + (lane & 15) * (D * ES) + (lane >> 4) * 16;
+    const char *vp = static_cast<const char *>(a.v) + blk + (lane >> 4) * (4 * D * ES) + (lane & 15) * (8 * ES);
+#pragma unroll
+    for (int i = 0; i < (FP8 ? 2 : 4); ++i) t.k[i] = *reinterpret_cast<const uint4 *>(kp + i * 64);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if constexpr (FP8)
+            t.v[e] = *reinterpret_cast<const uint2 *>(vp + e * (D * ES));
+        else
+            t.v[e] = *reinterpret_cast<const uint4 *>(vp + e * (D * ES));
+    }
+    if constexpr (FP8) {
+        t.ks = a.k_scale[phys * a.num_kv_heads + g];
+        t.vs = a.v_scale[phys * a.num_kv_heads + g];
+    } else {
+        t.ks = 1.f;
+        t.vs = 1.f;
+    }
+}
+
+// NB    16-row blocks of query rows the kernel is compiled for (covers max_q_len * G rows)
+// NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
+// OCC   wavefronts per SIMD the register budget is sized for
+template <int G, int NB, bool FP8, int NBUF, int OCC>
+__global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(AttnArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+    const int r16 = lane & 15, jq = lane >> 4;
+
+    const int num_waves = a.plan->num_waves;
+    const long long total = a.plan->total_tiles;
+    if (wave >= num_waves) return;
+    long long x = (long long)wave * total / num_waves;             // first tile of this span
+    const long long x_end = (long long)(wave + 1) * total / num_waves;
+    if (x >= x_end) return;
+
+    // request holding tile x: largest b with Hkv * tile_prefix[b] <= x
+    const long long per_head_x = x / a.num_kv_heads;  // tile_prefix[b] <= x / Hkv  <=>  Hkv*prefix <= x
+    int b = -1;
+    for (int base = 0; base <= a.batch; base += 64) {
+        const int idx = base + lane;
+        const bool le = idx <= a.batch && (long long)a.tile_prefix[idx] <= per_head_x;
+        b += __popcll(__ballot(le));
+    }
+    if (b >= a.batch) b = a.batch - 1;  // x < total, so this only guards against bad plans
+    int pre = a.tile_prefix[b];
+    int nb_tiles = a.tile_prefix[b + 1] - pre;
+    long long rem = x - (long long)pre * a.num_kv_heads;
+    int g = (int)(rem / nb_tiles);
+    int tile = (int)(rem % nb_tiles);
+
+    while (x < x_end) {
+        // ---- one unit segment: request b, kv head g, tiles [tile, t1) ----
+        const int left = (int)((x_end - x) < (long long)(nb_tiles - tile) ? (x_end - x) : (nb_tiles - tile));
+        const int t1 = tile + left;
+        const int L = a.kv_len[b];
+        const int q0 = a.q_indptr[b];
+        const int q_len = a.q_indptr[b + 1] - q0;
+        const int rows = q_len * G;
+        const int nbu = (rows + 15) >> 4;
+        const int32_t *bt = a.block_table + (long long)b * a.max_blocks;
+
+        // Q as B operand: lane holds row n = 16*nb + r16, 8 consecutive d per k-step
+        bf16x8 qreg[NB][4];
+        int lim[NB];  // last visible cache position of this lane's row in block nb
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = nb * 16 + r16;
+            const bool ok = n < rows;
+            const int qi = n / G, hh = n % G;
+            lim[nb] = ok ? L - q_len + qi : L - 1;
+            const char *qp = static_cast<const char *>(a.q) +
+                             (((long long)(q0 + qi) * a.num_q_heads + g * G + hh) * D) * 2;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const int d0 = FP8 ? ((ks >> 1) * 64 + jq * 16 + (ks & 1) * 8) : (ks * 32 + jq * 8);
+                uint4 w = make_uint4(0, 0, 0, 0);
+                if (ok && nb < nbu) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
+                qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
+
+        float m_run[NB], l_run[NB];
+        float4v acc[8][NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            m_run[nb] = -INFINITY;
+            l_run[nb] = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+        }
+        const float sc2 = a.sm_scale * kLog2e;
+        const int mask_from = L - q_len + 1;  // tiles reaching this position need masking
+
+        auto compute = [&](const TileRegs<FP8> &t, int ti) {
+            // K operand registers
+            bf16x8 kop[4];
+            if constexpr (FP8) {
+                kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
+                kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
+                kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
+                kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
+            }
+            // V operand registers: vop[mb] = d-phase mb of tokens 4*jq .. 4*jq+3
+            uint4 vw[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (FP8)
+                    vw[e] = fp8x8_to_bf16x8(t.v[e].x, t.v[e].y);
+                else
+                    vw[e] = t.v[e];
+            }
+            const bool need_mask = (ti + 1) * kTile > mask_from;
+            if (need_mask) {
+                // tokens at or past kv_len may hold anything: zero their V so that 0 * garbage cannot poison O
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (ti * kTile + jq * 4 + e >= L) vw[e] = make_uint4(0, 0, 0, 0);
+            }
+            short4v vop[8];
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) {
+                const uint32_t w0 = (&vw[0].x)[mb >> 1], w1 = (&vw[1].x)[mb >> 1];
+                const uint32_t w2 = (&vw[2].x)[mb >> 1], w3 = (&vw[3].x)[mb >> 1];
+                uint2 pk;
+                if (mb & 1) {
+                    pk.x = pack_hi16(w0, w1);
+                    pk.y = pack_hi16(w2, w3);
+                } else {
+                    pk.x = pack_lo16(w0, w1);
+                    pk.y = pack_lo16(w2, w3);
+                }
+                vop[mb] = __builtin_bit_cast(short4v, pk);
+            }
+            const float kscale = sc2 * t.ks;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                if (nb < nbu) {
+                    float4v s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s, 0, 0, 0);
+                    float sv[4] = {s.x * kscale, s.y * kscale, s.z * kscale, s.w * kscale};
+                    if (need_mask) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (ti * kTile + jq * 4 + e > lim[nb]) sv[e] = -INFINITY;
+                    }
+                    float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(m_run[nb], mx);
+                    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                    const float alpha = exp2f(m_run[nb] - m_use);
+                    float p[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) p[e] = exp2f(sv[e] - m_use);
+                    l_run[nb] = l_run[nb] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+                    m_run[nb] = m_new;
+                    if (__any(alpha != 1.0f)) {
+#pragma unroll
+                        for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
+                    }
+                    uint2 pk;
+                    {
+                        const __bf16 b0 = (__bf16)(p[0] * t.vs), b1 = (__bf16)(p[1] * t.vs);
+                        const __bf16 b2 = (__bf16)(p[2] * t.vs), b3 = (__bf16)(p[3] * t.vs);
+                        pk.x = (uint32_t)__builtin_bit_cast(uint16_t, b0) | ((uint32_t)__builtin_bit_cast(uint16_t, b1) << 16);
+                        pk.y = (uint32_t)__builtin_bit_cast(uint16_t, b2) | ((uint32_t)__builtin_bit_cast(uint16_t, b3) << 16);
+                    }
+                    const short4v pop = __builtin_bit_cast(short4v, pk);
+#pragma unroll
+                    for (int mb = 0; mb < 8; ++mb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
+                }
+            }
+        };
+
+        // block-table window: lane j holds the physical id of tile win0 + j
+        int win0 = tile;
+        int win = (win0 + lane < nb_tiles) ? bt[win0 + lane] : 0;
+        auto phys_of = [&](int ti) -> long long {
+            if (ti - win0 >= 64) {
+                win0 += 64;
+                win = (win0 + lane < nb_tiles) ? bt[win0 + lane] : 0;
+            }
+            return (long long)__builtin_amdgcn_readlane(win, ti - win0);
+        };
+
+        // software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers)
+        TileRegs<FP8> buf[NBUF];
+#pragma unroll
+        for (int j = 0; j < NBUF - 1; ++j)
+            if (tile + j < t1) load_tile<FP8>(buf[j], a, phys_of(tile + j), g, lane);
+        for (int base = tile; base < t1; base += NBUF) {
+#pragma unroll
+            for (int j = 0; j < NBUF; ++j) {
+                const int ti = base + j;
+                if (ti < t1) {
+                    if (ti + NBUF - 1 < t1)
+                        load_tile<FP8>(buf[(j + NBUF - 1) % NBUF], a, phys_of(ti + NBUF - 1), g, lane);
+                    compute(buf[j], ti);
+                }
+            }
+        }
+
+        // ---- partial result of this segment -> slot wave + unit ----
+        const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
+        float *po = a.part_o + slot * a.rows_pad * D;
+        float *pml = a.part_ml + slot * a.rows_pad * 2;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            if (nb < nbu) {
+                float l = l_run[nb];
+                l += __shfl_xor(l, 16);
+                l += __shfl_xor(l, 32);
+                const int n = nb * 16 + r16;
+                if (n < rows) {
+                    if (jq == 0) {
+                        pml[n * 2 + 0] = m_run[nb];
+                        pml[n * 2 + 1] = l;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        // accumulator row 4*jq+e of M-block mb is d = 8*(4*jq+e) + mb
+                        float *dst = po + n * D + (jq * 4 + e) * 8;
+                        float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+                        float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
+                        *reinterpret_cast<float4v *>(dst) = lo;
+                        *reinterpret_cast<float4v *>(dst + 4) = hi;
+                    }
+                }
+            }
+        }
+
+        // ---- advance to the next unit ----
+        x += left;
+        tile = 0;
+        if (++g == a.num_kv_heads) {
+            g = 0;
+            ++b;
+            if (b < a.batch) {
+                pre = a.tile_prefix[b];
+                nb_tiles = a.tile_prefix[b + 1] - pre;
+            }
+        }
+        if (b >= a.batch) break;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// merge: one workgroup per unit
+// ---------------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+{
+    const int unit = blockIdx.x;
+    const int b = unit / a.num_kv_heads, g = unit % a.num_kv_heads;
+    const long long total = a.plan->total_tiles;
+    const long long nw = a.plan->num_waves;
+    const int pre = a.tile_prefix[b];
+    const int nb_tiles = a.tile_prefix[b + 1] - pre;
+    const long long off = (long long)pre * a.num_kv_heads + (long long)g * nb_tiles;
+    // wave w covers tiles [w*total/nw, (w+1)*total/nw); the last wave starting at or before tile t
+    // is ((t+1)*nw - 1) / total
+    const int w_first = (int)(((off + 1) * nw - 1) / total);
+    const int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
+    const int q0 = a.q_indptr[b];
+    const int q_len = a.q_indptr[b + 1] - q0;
+    const int rows = q_len * G;
+
+    for (int item = threadIdx.x; item < rows * (D / 4); item += 256) {
+        const int n = item / (D / 4), d4 = item % (D / 4);
+        float m_all = -INFINITY;
+        for (int w = w_first; w <= w_last; ++w) {
+            const long long slot = (long long)w + unit;
+            m_all = fmaxf(m_all, a.part_ml[(slot * a.rows_pad + n) * 2]);
+        }
+        float l_all = 0.f;
+        float4v o = {0.f, 0.f, 0.f, 0.f};
+        for (int w = w_first; w <= w_last; ++w) {
+            const long long slot = (long long)w + unit;
+            const float mp = a.part_ml[(slot * a.rows_pad + n) * 2];
+            const float lp = a.part_ml[(slot * a.rows_pad + n) * 2 + 1];
+            const float wgt = (mp == -INFINITY) ? 0.f : exp2f(mp - m_all);
+            l_all += wgt * lp;
+            if (wgt != 0.f) {
+                const float4v op = *reinterpret_cast<const float4v *>(a.part_o + (slot * a.rows_pad + n) * D + d4 * 4);
+                o += op * wgt;
+            }
+        }
+        const float inv = 1.f / l_all;
+        const int qi = n / G, hh = n % G;
+        const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
+        __bf16 *dst = static_cast<__bf16 *>(a.out) + orow * D + d4 * 4;
+        uint2 pk;
+        const __bf16 b0 = (__bf16)(o.x * inv), b1 = (__bf16)(o.y * inv), b2 = (__bf16)(o.z * inv), b3 = (__bf16)(o.w * inv);
+        pk.x = (uint32_t)__builtin_bit_cast(uint16_t, b0) | ((uint32_t)__builtin_bit_cast(uint16_t, b1) << 16);
+        pk.y = (uint32_t)__builtin_bit_cast(uint16_t, b2) | ((uint32_t)__builtin_bit_cast(uint16_t, b3) << 16);
+        *reinterpret_cast<uint2 *>(dst) = pk;
+        if (a.lse && d4 == 0) a.lse[orow] = (m_all + log2f(l_all)) * kLn2;
+    }
+}
+
+template <int G, int NB, bool FP8>
+int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
+{
+    // Up to two row blocks fit the register file twice per SIMD; beyond that one wave per SIMD
+    // with a deeper ring keeps the same number of bytes in flight per compute unit.
+    constexpr int OCC = NB <= 2 ? 2 : 1;
+    constexpr int NBUF = NB <= 2 ? 2 : (FP8 ? 4 : 3);
+    AttnArgs b = a;
+    b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
+    b.launch_waves -= b.launch_waves % kWavesPerWg;
+    if (b.launch_waves < kWavesPerWg) b.launch_waves = kWavesPerWg;
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, stream, b);
+    SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
+    if (ev0) SS_HIP_CHECK(hipEventRecord(ev0, stream), "hipEventRecord");
+    hipLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
+                       dim3(64 * kWavesPerWg), 0, stream, b);
+    SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
+    if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
+    hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
+    SS_HIP_CHECK(hipGetLastError(), "launch attn_merge_kernel");
+    return SS_OK;
+}
+
+template <int G, int NB>
+int32_t launch_nb(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
+{
+    if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true>(a, stream, ev0, ev1);
+    return launch_stream<G, NB, false>(a, stream, ev0, ev1);
+}
+
+template <int G>
+int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
+{
+    constexpr int NBMAX = (SS_OUT_WIDTH * G + 15) / 16;
+    const int nb = (a.max_q_len * G + 15) / 16;
+    if constexpr (NBMAX >= 5) if (nb == 5) return launch_nb<G, 5>(a, stream, ev0, ev1);
+    if constexpr (NBMAX >= 4) if (nb == 4) return launch_nb<G, 4>(a, stream, ev0, ev1);
+    if constexpr (NBMAX >= 3) if (nb == 3) return launch_nb<G, 3>(a, stream, ev0, ev1);
+    if constexpr (NBMAX >= 2) if (nb == 2) return launch_nb<G, 2>(a, stream, ev0, ev1);
+    return launch_nb<G, 1>(a, stream, ev0, ev1);
+}
+
+}  // namespace
+
+size_t attn_workspace_bytes(int batch, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves)
+{
+    const int G = num_q_heads / num_kv_heads;
+    const size_t rows_pad = align_up((size_t)SS_OUT_WIDTH * G, 16);
+    const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
+    size_t n = 256;
+    n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);
+    n += align_up(slots * rows_pad * 2 * sizeof(float), 256);
+    n += align_up(slots * rows_pad * (size_t)head_dim * sizeof(float), 256);
+    return n;
+}
+
+bool attn_mfma_supported(const AttnArgs &a)
+{
+    const int G = a.num_q_heads / a.num_kv_heads;
+    return a.head_dim == D && a.q_dtype == SS_BF16 && (a.kv_dtype == SS_BF16 || a.kv_dtype == SS_FP8_E4M3) &&
+           (G == 1 || G == 2 || G == 4 || G == 8) && a.launch_waves % kWavesPerWg == 0;
+}
+
+int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
+{
+    switch (a.num_q_heads / a.num_kv_heads) {
+    case 1: return launch_for_group<1>(a, stream, ev0, ev1);
+    case 2: return launch_for_group<2>(a, stream, ev0, ev1);
+    case 4: return launch_for_group<4>(a, stream, ev0, ev1);
+    case 8: return launch_for_group<8>(a, stream, ev0, ev1);
+    default: return fail(SS_ERR_UNSUPPORTED, "head grouping not built for the MFMA kernel");
+    }
+}
+
+}  // namespace ss

@@ -1,0 +1,83 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "specverify.h"
+
+namespace ss {
+
+// ---- error reporting ---------------------------------------------------------------------
+int32_t fail(int32_t code, const char *fmt, ...);   // stores the thread's message, returns code
+int32_t hip_fail(hipError_t e, const char *what);   // SS_ERR_DEVICE with the HIP text
+
+#define SS_HIP_CHECK(expr, what)                      \
+    do {                                              \
+        hipError_t e__ = (expr);                      \
+        if (e__ != hipSuccess) return ss::hip_fail(e__, what); \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- attention -----------------------------------------------------------------------------
+constexpr int kTile = SS_BLOCK_SIZE;     // tokens per KV tile = tokens per cache block
+constexpr int kWavesPerWg = 4;
+constexpr int kMinTilesPerWave = 8;      // below this a KV partition is not worth its partial write
+
+// Written by the plan kernel, read by the streaming and merge kernels.
+struct AttnPlan {
+    int32_t total_tiles;   // sum over requests of ceil(kv_len/16) * num_kv_heads
+    int32_t num_waves;     // partitions actually used (<= launched wavefronts)
+    int32_t pad[2];
+};
+
+struct AttnArgs {
+    // cache
+    const void *k, *v;
+    const float *k_scale, *v_scale;
+    int32_t num_kv_heads, head_dim, kv_dtype;
+    // batch
+    int32_t batch, max_blocks;
+    const int32_t *block_table, *kv_len, *q_indptr;
+    // query / output
+    const void *q;
+    void *out;
+    float *lse;
+    int32_t q_dtype, num_q_heads, total_rows, max_q_len;
+    float sm_scale;
+    // workspace carve-up
+    AttnPlan *plan;
+    int32_t *tile_prefix;  // [batch+1] exclusive prefix of ceil(kv_len/16)
+    float *part_o;         // [slots][rows_pad][head_dim]
+    float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
+    int32_t rows_pad;      // query rows per (request, kv head), padded to 16
+    int32_t launch_waves;  // upper bound of streaming wavefronts (sizes the partial slots)
+};
+
+size_t attn_workspace_bytes(int batch, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves);
+bool attn_mfma_supported(const AttnArgs &a);
+int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
+int32_t attn_generic_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
+int attn_default_waves();
+
+// ---- accept --------------------------------------------------------------------------------
+constexpr int kChunk = 8192;  // vocabulary entries per workgroup in the streaming passes
+
+struct AcceptArgs {
+    int32_t batch, vocab, logit_dtype, total_rows, greedy;
+    int64_t row_stride;
+    const int32_t *q_indptr;
+    const void *target, *draft;
+    const int32_t *draft_tokens;
+    const float *u_accept, *u_sample, *temperature;
+    float temperature_scalar;
+    int32_t *accepted_len, *out_tokens;
+    float *ratio_out;
+    void *workspace;
+};
+size_t accept_workspace_bytes(int batch, int total_rows, int vocab);
+int32_t accept_launch(const AcceptArgs &a, hipStream_t stream);
+
+}  // namespace ss
