@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify step (spec_verify_attn + spec_accept) on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic batch: the KV
+plan, the KV-streaming attention kernel, the partial merge, and the five accept
+passes.  Inputs are resident in HBM before the timed region; several copies of
+the cache and logits are rotated so the last-level cache cannot serve the stream.
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def cpu_baseline(cfg, att, acc, budget_requests: int):
+    """The oracle as it stands, timed on this host on the first `budget_requests` requests."""
+    import oracle
+    n = min(budget_requests, att["batch"])
+    reqs = list(range(n))
+    sub = dict(acc)
+    rows = int(acc["q_indptr"][n])
+    sub.update(batch=n, total_rows=rows, q_indptr=acc["q_indptr"][:n + 1], depth=acc["depth"][:n],
+               target_logits=acc["target_logits"][:rows], draft_logits=acc["draft_logits"][:max(rows - n, 0)],
+               draft_tokens=acc["draft_tokens"][:rows - n], u_accept=acc["u_accept"][:rows - n],
+               u_sample=acc["u_sample"][:n], temperature=acc["temperature"][:n])
+    t0 = time.perf_counter()
+    oracle.verify_attn(att, requests=reqs)
+    t1 = time.perf_counter()
+    oracle.spec_accept(sub)
+    t2 = time.perf_counter()
+    toks = rows
+    return dict(value=toks / (t2 - t0), unit="verified tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"first {n} of {att['batch']} requests ({toks} query tokens): attention {t1 - t0:.2f} s, "
+                       f"accept {t2 - t1:.2f} s")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="llama3_8b_b64")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--rotate", type=int, default=4, help="distinct copies of cache and logits cycled through")
+    ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the verify step of one decode lane); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_09562_amd import binding, synth
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_09562_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        return 3
+    cfg = synth.config_by_name(args.config)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    att = synth.make_attention_inputs(cfg, seed=args.seed)
+    acc = synth.make_accept_inputs(cfg, seed=args.seed, depth=att["depth"])
+    max_q_len = int(att["depth"].max()) + 1
+    kv_bytes = synth.kv_bytes_algorithmic(att)
+    q_tokens = int(att["total_rows"])
+
+    # device copies (rotated), outputs and workspaces allocated once
+    nrot = max(1, args.rotate)
+    d_att = [binding.attention_to_device(att, dev) for _ in range(nrot)]
+    d_acc = [binding.accept_to_device(acc, dev) for _ in range(nrot)]
+    out, lse, ws_att = binding.alloc_attention_outputs(d_att[0], dev, max_q_len=max_q_len)
+    n_acc, toks, ratio, ws_acc = binding.alloc_accept_outputs(d_acc[0], dev)
+
+    def step(i: int) -> None:
+        binding.ss_spec_verify_attn(d_att[i % nrot], out, lse, ws_att, max_q_len=max_q_len)
+        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    binding.ss_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = binding.ss_profile_collect(args.steps)
+    elapsed = t1 - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-call breakdown (outside the timed region)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_att, t_acc, t_greedy = [], [], []
+    for i in range(10):
+        ev[0].record()
+        binding.ss_spec_verify_attn(d_att[i % nrot], out, lse, ws_att, max_q_len=max_q_len)
+        ev[1].record()
+        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_att.append(ev[0].elapsed_time(ev[1]))
+        t_acc.append(ev[1].elapsed_time(ev[2]))
+    accepted = n_acc.cpu().numpy()
+    g_acc, g_toks = torch.empty_like(n_acc), torch.empty_like(toks)
+    for i in range(6):
+        ev[0].record()
+        binding.ss_spec_accept(d_acc[i % nrot], g_acc, g_toks, None, ws_acc, greedy=True)
+        ev[1].record()
+        torch.cuda.synchronize()
+        t_greedy.append(ev[0].elapsed_time(ev[1]))
+
+    kern_avg_ms = float(np.mean(kern_ms)) if len(kern_ms) else float("nan")
+    achieved = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+    esz = 2 if cfg.logit_dtype == "bf16" else 4
+    accept_bytes = (2 * q_tokens - att["batch"]) * cfg.vocab * esz
+    result = {
+        "metric": "verified tokens/s + KV read GB/s (% HBM peak), spec_verify_attn+accept, 1 GPU",
+        "value": q_tokens * args.steps / elapsed,
+        "unit": "verified tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp8": "fp8_e4m3", "f32": "f32"}[cfg.kv_dtype], "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": att["batch"], "num_q_heads": cfg.num_q_heads,
+                   "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "query_tokens": q_tokens,
+                   "kv_tokens": int(att["kv_len"].astype(np.int64).sum()), "vocab": cfg.vocab,
+                   "max_q_len": max_q_len, "rotated_copies": nrot, "seed": args.seed},
+        "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": kv_bytes, "kernel_ms_avg": kern_avg_ms,
+                     "kernel_ms_min": float(np.min(kern_ms)) if len(kern_ms) else None, "launches": int(len(kern_ms))},
+        "kv_read_gbps": achieved, "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
+        "t_attn_ms": float(np.median(t_att)), "t_accept_ms": float(np.median(t_acc)),
+        "t_accept_greedy_ms": float(np.median(t_greedy)),
+        "accept_pass1_gbps": accept_bytes / (float(np.median(t_acc)) * 1e-3) / 1e9,
+        "emitted_tokens_per_s": float((accepted + 1).sum()) * args.steps / elapsed,
+        "mean_accepted_len": float(accepted.mean()),
+    }
+    if not args.no_check:
+        # spot check after timing: the timed path must still agree with the oracle on one request
+        import oracle
+        b = int(np.argmax(att["kv_len"]))
+        ref, _ = oracle.verify_attn(att, requests=[b])
+        got = binding.bf16_bits_to_float(out) if cfg.q_dtype != "f32" else out.cpu().numpy().astype(np.float64)
+        r0, r1 = att["q_indptr"][b], att["q_indptr"][b + 1]
+        err = float(np.max(np.abs(got[r0:r1] - ref[r0:r1])))
+        result["spot_check_max_abs_err"] = err
+        tol = 6e-2 if cfg.kv_dtype == "fp8" else 2e-2
+        if not err <= tol + 1e-2 * float(np.max(np.abs(ref[r0:r1]))):
+            print(f"bench.py: parity spot check failed (max abs err {err})", file=sys.stderr)
+            return 4
+    if args.cpu_requests > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, att, acc, args.cpu_requests)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
