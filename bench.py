@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=4, help="distinct copies of cache and logits cycled through")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
+    ap.add_argument("--attn-waves", type=int, default=0, help="KV partitions of the attention kernel (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the verify step of one decode lane); "
@@ -72,6 +73,8 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 3
     cfg = synth.config_by_name(args.config)
+    if args.attn_waves:
+        binding.ss_set_option("attn_waves", args.attn_waves)
     dev = "cuda:0"
     torch.cuda.set_device(0)
 

@@ -26,6 +26,7 @@ namespace ss {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float2v __attribute__((ext_vector_type(2)));
@@ -33,6 +34,8 @@ typedef float float2v __attribute__((ext_vector_type(2)));
 constexpr int D = 128;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
+constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
 
 // ---------------------------------------------------------------------------------------------
 // plan: tile prefix over requests, total tiles, number of partitions
@@ -112,8 +115,12 @@ struct TileRegs {
     float ks, vs;  // block scales (fp8), 1 otherwise
 };
 
+// All loads of one tile are vector loads issued back to back, so one counter orders them and the
+// consumer can wait for exactly this tile.  `vzero` is a lane register holding 0 that the compiler
+// cannot see through: it keeps the (wave-uniform) scale reads on the vector path too.
 template <bool FP8>
-__device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, int64_t phys, int g, int lane)
+__device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, const float *__restrict__ k_scale,
+                                          const float *__restrict__ v_scale, int64_t phys, int g, int lane, int vzero)
 {
     constexpr int ES = FP8 ? 1 : 2;
     const int64_t blk = (phys * a.num_kv_heads + g) * (int64_t)(kTile * D * ES);
@@ -129,8 +136,8 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, i
             t.v[e] = *reinterpret_cast<const uint4 *>(vp + e * (D * ES));
     }
     if constexpr (FP8) {
-        t.ks = a.k_scale[phys * a.num_kv_heads + g];
-        t.vs = a.v_scale[phys * a.num_kv_heads + g];
+        t.ks = k_scale[phys * a.num_kv_heads + g + vzero];
+        t.vs = v_scale[phys * a.num_kv_heads + g + vzero];
     } else {
         t.ks = 1.f;
         t.vs = 1.f;
@@ -141,11 +148,19 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, i
 // NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
 // OCC   wavefronts per SIMD the register budget is sized for
 template <int G, int NB, bool FP8, int NBUF, int OCC>
-__global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
+    AttnArgs a, const int32_t *__restrict__ block_table, const int32_t *__restrict__ tile_prefix,
+    const int32_t *__restrict__ kv_len, const int32_t *__restrict__ q_indptr, const float *__restrict__ k_scale,
+    const float *__restrict__ v_scale)
 {
+    // The metadata arrays come in as separate no-alias arguments so that their wave-uniform reads
+    // become scalar loads (own counter, no ordering against the vector KV loads).
     const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+    const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave = blockIdx.x * kWavesPerWg + wslot;
     const int r16 = lane & 15, jq = lane >> 4;
+    int vzero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
 
     const int num_waves = a.plan->num_waves;
     const long long total = a.plan->total_tiles;
@@ -159,12 +174,12 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
     int b = -1;
     for (int base = 0; base <= a.batch; base += 64) {
         const int idx = base + lane;
-        const bool le = idx <= a.batch && (long long)a.tile_prefix[idx] <= per_head_x;
+        const bool le = idx <= a.batch && (long long)tile_prefix[idx] <= per_head_x;
         b += __popcll(__ballot(le));
     }
     if (b >= a.batch) b = a.batch - 1;  // x < total, so this only guards against bad plans
-    int pre = a.tile_prefix[b];
-    int nb_tiles = a.tile_prefix[b + 1] - pre;
+    int pre = tile_prefix[b];
+    int nb_tiles = tile_prefix[b + 1] - pre;
     long long rem = x - (long long)pre * a.num_kv_heads;
     int g = (int)(rem / nb_tiles);
     int tile = (int)(rem % nb_tiles);
@@ -173,12 +188,12 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
         // ---- one unit segment: request b, kv head g, tiles [tile, t1) ----
         const int left = (int)((x_end - x) < (long long)(nb_tiles - tile) ? (x_end - x) : (nb_tiles - tile));
         const int t1 = tile + left;
-        const int L = a.kv_len[b];
-        const int q0 = a.q_indptr[b];
-        const int q_len = a.q_indptr[b + 1] - q0;
+        const int L = kv_len[b];
+        const int q0 = q_indptr[b];
+        const int q_len = q_indptr[b + 1] - q0;
         const int rows = q_len * G;
         const int nbu = (rows + 15) >> 4;
-        const int32_t *bt = a.block_table + (long long)b * a.max_blocks;
+        const int32_t *__restrict__ bt = block_table + (long long)b * a.max_blocks;
 
         // Q as B operand: lane holds row n = 16*nb + r16, 8 consecutive d per k-step
         bf16x8 qreg[NB][4];
@@ -195,7 +210,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
             for (int ks = 0; ks < 4; ++ks) {
                 const int d0 = FP8 ? ((ks >> 1) * 64 + jq * 16 + (ks & 1) * 8) : (ks * 32 + jq * 8);
                 uint4 w = make_uint4(0, 0, 0, 0);
-                if (ok && nb < nbu) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
+                if (ok) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
                 qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
             }
         }
@@ -204,16 +219,48 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
         float4v acc[8][NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            m_run[nb] = -INFINITY;
+            m_run[nb] = kNoMax;
             l_run[nb] = 0.f;
 #pragma unroll
             for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
         }
         const float sc2 = a.sm_scale * kLog2e;
-        const int mask_from = L - q_len + 1;  // tiles reaching this position need masking
 
+        // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond this
+        // unit's rows hold zero queries; they are computed anyway (cheaper than branching) and never
+        // stored.  The body is straight-line code apart from the rare rescale: masks are selects that
+        // are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
+        // its result: the wait states the hardware needs there are only inserted inside a block.)
         auto compute = [&](const TileRegs<FP8> &t, int ti) {
-            // K operand registers
+            const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
+            // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
+            // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
+            const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
+            const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
+            short4v vop[8];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {   // word h of each token's 8 values holds d-phases 2h and 2h+1
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (FP8) {
+                        const uint32_t src = (h < 2) ? t.v[e].x : t.v[e].y;   // two e4m3 bytes -> two bf16, exact
+                        const float2v f = (h & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true)
+                                                  : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
+                        w[e] = pack_hi16(__float_as_uint(f.x), __float_as_uint(f.y));
+                    } else {
+                        w[e] = (&t.v[e].x)[h];
+                    }
+                }
+                uint2 lo, hi;
+                lo.x = pack_lo16(w[0], w[1]) & m01;
+                lo.y = pack_lo16(w[2], w[3]) & m23;
+                hi.x = pack_hi16(w[0], w[1]) & m01;
+                hi.y = pack_hi16(w[2], w[3]) & m23;
+                vop[2 * h] = __builtin_bit_cast(short4v, lo);
+                vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
+            }
+
             bf16x8 kop[4];
             if constexpr (FP8) {
                 kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
@@ -224,110 +271,102 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
             }
-            // V operand registers: vop[mb] = d-phase mb of tokens 4*jq .. 4*jq+3
-            uint4 vw[4];
+            float4v s[NB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if constexpr (FP8)
-                    vw[e] = fp8x8_to_bf16x8(t.v[e].x, t.v[e].y);
-                else
-                    vw[e] = t.v[e];
-            }
-            const bool need_mask = (ti + 1) * kTile > mask_from;
-            if (need_mask) {
-                // tokens at or past kv_len may hold anything: zero their V so that 0 * garbage cannot poison O
+            for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (ti * kTile + jq * 4 + e >= L) vw[e] = make_uint4(0, 0, 0, 0);
-            }
-            short4v vop[8];
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb) {
-                const uint32_t w0 = (&vw[0].x)[mb >> 1], w1 = (&vw[1].x)[mb >> 1];
-                const uint32_t w2 = (&vw[2].x)[mb >> 1], w3 = (&vw[3].x)[mb >> 1];
-                uint2 pk;
-                if (mb & 1) {
-                    pk.x = pack_hi16(w0, w1);
-                    pk.y = pack_hi16(w2, w3);
-                } else {
-                    pk.x = pack_lo16(w0, w1);
-                    pk.y = pack_lo16(w2, w3);
-                }
-                vop[mb] = __builtin_bit_cast(short4v, pk);
-            }
+                for (int nb = 0; nb < NB; ++nb)
+                    s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
+
+            // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
+            // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
+            // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
             const float kscale = sc2 * t.ks;
+            float sv[NB][4];
+            bool trig = false;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                if (nb < nbu) {
-                    float4v s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s, 0, 0, 0);
-                    float sv[4] = {s.x * kscale, s.y * kscale, s.z * kscale, s.w * kscale};
-                    if (need_mask) {
+                for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                    sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+                const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+                trig |= lane_mx > m_run[nb] + kSlack;
+            }
+            if (__any(trig)) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (ti * kTile + jq * 4 + e > lim[nb]) sv[e] = -INFINITY;
-                    }
-                    float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+                for (int nb = 0; nb < NB; ++nb) {
+                    float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
                     mx = fmaxf(mx, __shfl_xor(mx, 16));
                     mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m_run[nb], mx);
-                    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                    const float alpha = exp2f(m_run[nb] - m_use);
-                    float p[4];
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+                    l_run[nb] *= alpha;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) p[e] = exp2f(sv[e] - m_use);
-                    l_run[nb] = l_run[nb] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+                    for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
                     m_run[nb] = m_new;
-                    if (__any(alpha != 1.0f)) {
-#pragma unroll
-                        for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
-                    }
-                    uint2 pk;
-                    {
-                        const __bf16 b0 = (__bf16)(p[0] * t.vs), b1 = (__bf16)(p[1] * t.vs);
-                        const __bf16 b2 = (__bf16)(p[2] * t.vs), b3 = (__bf16)(p[3] * t.vs);
-                        pk.x = (uint32_t)__builtin_bit_cast(uint16_t, b0) | ((uint32_t)__builtin_bit_cast(uint16_t, b1) << 16);
-                        pk.y = (uint32_t)__builtin_bit_cast(uint16_t, b2) | ((uint32_t)__builtin_bit_cast(uint16_t, b3) << 16);
-                    }
-                    const short4v pop = __builtin_bit_cast(short4v, pk);
-#pragma unroll
-                    for (int mb = 0; mb < 8; ++mb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
                 }
             }
-        };
-
-        // block-table window: lane j holds the physical id of tile win0 + j
-        int win0 = tile;
-        int win = (win0 + lane < nb_tiles) ? bt[win0 + lane] : 0;
-        auto phys_of = [&](int ti) -> long long {
-            if (ti - win0 >= 64) {
-                win0 += 64;
-                win = (win0 + lane < nb_tiles) ? bt[win0 + lane] : 0;
+            short4v pop[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float p[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
+                l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+                const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+                uint2 pk;
+                pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+                pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+                pop[nb] = __builtin_bit_cast(short4v, pk);
             }
-            return (long long)__builtin_amdgcn_readlane(win, ti - win0);
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb], acc[mb][nb], 0, 0, 0);
         };
 
-        // software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers)
+        auto issue = [&](TileRegs<FP8> &t, int tt) {
+            load_tile<FP8>(t, a, k_scale, v_scale, (long long)bt[tt], g, lane, vzero);
+        };
+        // Software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers).
+        // The steady-state loop issues its prefetch unconditionally, so the wait before each
+        // compute only covers the tile it needs and NBUF-1 tiles stay in flight; the last few
+        // tiles of a segment (and short segments) run through a conditional epilogue.
         TileRegs<FP8> buf[NBUF];
+        int ti = tile;
+        if (t1 - tile >= 2 * NBUF - 1) {
 #pragma unroll
-        for (int j = 0; j < NBUF - 1; ++j)
-            if (tile + j < t1) load_tile<FP8>(buf[j], a, phys_of(tile + j), g, lane);
-        for (int base = tile; base < t1; base += NBUF) {
+            for (int j = 0; j < NBUF - 1; ++j) issue(buf[j], tile + j);
+            for (; ti + 2 * NBUF - 2 < t1; ti += NBUF) {
 #pragma unroll
-            for (int j = 0; j < NBUF; ++j) {
-                const int ti = base + j;
-                if (ti < t1) {
-                    if (ti + NBUF - 1 < t1)
-                        load_tile<FP8>(buf[(j + NBUF - 1) % NBUF], a, phys_of(ti + NBUF - 1), g, lane);
-                    compute(buf[j], ti);
+                for (int j = 0; j < NBUF; ++j) {
+                    issue(buf[(j + NBUF - 1) % NBUF], ti + j + NBUF - 1);
+                    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
+                    compute(buf[j], ti + j);
                 }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NBUF - 1; ++j)
+                if (tile + j < t1) issue(buf[j], tile + j);
+        }
+        // here buf[j] holds tile ti + j for j < NBUF-1 (as far as such tiles exist)
+#pragma unroll
+        for (int j = 0; j < 2 * NBUF - 2; ++j) {
+            if (ti + j < t1) {
+                if (ti + j + NBUF - 1 < t1) issue(buf[(j + NBUF - 1) % NBUF], ti + j + NBUF - 1);
+                compute(buf[j % NBUF], ti + j);
             }
         }
 
         // ---- partial result of this segment -> slot wave + unit ----
+        // The accumulators were last written by MFMAs in a different basic block: give them the wait
+        // states a read needs before anything below touches them.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
         const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
         float *po = a.part_o + slot * a.rows_pad * D;
         float *pml = a.part_ml + slot * a.rows_pad * 2;
@@ -363,8 +402,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(Attn
             g = 0;
             ++b;
             if (b < a.batch) {
-                pre = a.tile_prefix[b];
-                nb_tiles = a.tile_prefix[b + 1] - pre;
+                pre = tile_prefix[b];
+                nb_tiles = tile_prefix[b + 1] - pre;
             }
         }
         if (b >= a.batch) break;
@@ -405,7 +444,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
             const long long slot = (long long)w + unit;
             const float mp = a.part_ml[(slot * a.rows_pad + n) * 2];
             const float lp = a.part_ml[(slot * a.rows_pad + n) * 2 + 1];
-            const float wgt = (mp == -INFINITY) ? 0.f : exp2f(mp - m_all);
+            const float wgt = exp2f(mp - m_all);  // a partial that saw no visible token has m = -1e30, l = 0
             l_all += wgt * lp;
             if (wgt != 0.f) {
                 const float4v op = *reinterpret_cast<const float4v *>(a.part_o + (slot * a.rows_pad + n) * D + d4 * 4);
@@ -440,7 +479,8 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     if (ev0) SS_HIP_CHECK(hipEventRecord(ev0, stream), "hipEventRecord");
     hipLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
-                       dim3(64 * kWavesPerWg), 0, stream, b);
+                       dim3(64 * kWavesPerWg), 0, stream, b, b.block_table, b.tile_prefix, b.kv_len, b.q_indptr,
+                       b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
     if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
     hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
