@@ -1,13 +1,14 @@
 // spec_accept: acceptance walk and resampling over full-vocabulary logits.
 //
 // Pass 1 (rowstats) streams every target and draft row once (the HBM-bound part): per
-// 8192-entry chunk it leaves the chunk maximum and sum of exp2((x - max) * log2e/T) in fp32
+// 8192-entry chunk it leaves the chunk maximum and the sum of exp2((x - max) * log2e/T) in fp32
 // (greedy mode: maximum and lowest-index argmax of target rows only).
-// decide      one wavefront per request merges the chunk statistics, walks the drafts
-//             (u < p/q in fp64) and fixes the accepted length and which rows are resampled.
-// Passes 2a-2c touch only the one or two rows the new token is drawn from and work in fp64,
-// so the drawn token can be reproduced by an fp64 reference: 2a normalisers per chunk, 2b
-// residual mass per chunk, 2c inverse-CDF search inside the chunk that holds u * mass.
+// decide      one workgroup per request merges the chunk statistics of all its rows in parallel,
+//             evaluates u < p/q for every draft in fp64 and fixes the accepted length and the
+//             row(s) the new token is drawn from.
+// Passes 2a-2c touch only those one or two rows per request and work in fp64, so that the drawn
+// token can be reproduced by an fp64 reference: 2a normalisers per 2048-entry block, 2b residual
+// mass per block, 2c inverse-CDF search inside the block that holds u * mass.
 // All reductions have a fixed order (no atomics): results are run-to-run identical.
 #include "common.h"
 
@@ -15,7 +16,10 @@ namespace ss {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kPerThread = kChunk / kThreads;  // 32 logits per lane
+constexpr int kPerThread = kChunk / kThreads;  // 32 logits per lane in pass 1
+constexpr int kSub = 2048;                     // vocabulary entries per workgroup in the fp64 passes
+constexpr int kSubPer = kSub / kThreads;       // 8 logits per lane there
+constexpr int kMaxRows = 2 * SS_MAX_DEPTH + 1; // rows of one request: k+1 target, k draft
 constexpr double kLog2eD = 1.4426950408889634;
 
 struct RowPick {      // written by decide, read by the resampling passes
@@ -31,16 +35,18 @@ struct Workspace {
     float *cmax, *csum;   // [rows][nchunks]
     int32_t *carg;        // [rows][nchunks]
     RowPick *pick;        // [batch]
-    double *zp, *zq, *sc; // [batch][nchunks]
-    int nchunks, rows;
+    double *zp, *zq, *sc; // [batch][nsub]
+    int nchunks, nsub, rows;
 };
 
 __host__ __device__ inline int num_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
+__host__ __device__ inline int num_sub(int vocab) { return (vocab + kSub - 1) / kSub; }
 
 __host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
 {
     Workspace w;
     w.nchunks = num_chunks(vocab);
+    w.nsub = num_sub(vocab);
     w.rows = 2 * total_rows - batch;
     char *p = static_cast<char *>(ws);
     const size_t per = align_up(sizeof(float) * (size_t)w.rows * w.nchunks, 256);
@@ -48,33 +54,32 @@ __host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
     w.csum = reinterpret_cast<float *>(p); p += per;
     w.carg = reinterpret_cast<int32_t *>(p); p += per;
     w.pick = reinterpret_cast<RowPick *>(p); p += align_up(sizeof(RowPick) * (size_t)batch, 256);
-    const size_t perd = align_up(sizeof(double) * (size_t)batch * w.nchunks, 256);
+    const size_t perd = align_up(sizeof(double) * (size_t)batch * w.nsub, 256);
     w.zp = reinterpret_cast<double *>(p); p += perd;
     w.zq = reinterpret_cast<double *>(p); p += perd;
     w.sc = reinterpret_cast<double *>(p); p += perd;
     return w;
 }
 
-// ---- loading one lane's share of a chunk ---------------------------------------------------
-// Coalesced order: lane t owns elements chunk0 + it*(kThreads*8) + t*8 + j  (bf16, it<4, j<8)
-//                                   or chunk0 + it*(kThreads*4) + t*4 + j  (f32,  it<8, j<4)
-// Sequential order (sampling search): lane t owns chunk0 + t*32 .. +31.
+// ---- loading one lane's share of a block of N*256 vocabulary entries -------------------------
+// Coalesced order: lane t owns entries base + it*(256*vec) + t*vec + j (vec = 8 for bf16, 4 for f32).
+// Sequential order (the inverse-CDF search): lane t owns base + t*N .. + N-1.
 // Out-of-vocabulary positions read as -inf.  index_of() gives the vocabulary id of slot s.
-template <bool SEQ>
-__device__ __forceinline__ int index_of(int chunk0, int tid, int s, int dtype)
+template <int N, bool SEQ>
+__device__ __forceinline__ int index_of(int base, int tid, int s, int dtype)
 {
-    if (SEQ) return chunk0 + tid * kPerThread + s;
+    if (SEQ) return base + tid * N + s;
     const int vec = dtype == SS_BF16 ? 8 : 4;
-    return chunk0 + (s / vec) * (kThreads * vec) + tid * vec + (s % vec);
+    return base + (s / vec) * (kThreads * vec) + tid * vec + (s % vec);
 }
 
-template <bool SEQ>
-__device__ __forceinline__ void load_slots(const void *row, int vocab, int chunk0, int tid, int dtype, float (&x)[kPerThread])
+template <int N, bool SEQ>
+__device__ __forceinline__ void load_slots(const void *row, int vocab, int base, int tid, int dtype, float (&x)[N])
 {
     if (dtype == SS_BF16) {
 #pragma unroll
-        for (int it = 0; it < kPerThread / 8; ++it) {
-            const int i0 = index_of<SEQ>(chunk0, tid, it * 8, dtype);
+        for (int it = 0; it < N / 8; ++it) {
+            const int i0 = index_of<N, SEQ>(base, tid, it * 8, dtype);
             if (i0 + 8 <= vocab) {
                 const uint4 w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + i0);
                 const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
@@ -93,8 +98,8 @@ __device__ __forceinline__ void load_slots(const void *row, int vocab, int chunk
         }
     } else {
 #pragma unroll
-        for (int it = 0; it < kPerThread / 4; ++it) {
-            const int i0 = index_of<SEQ>(chunk0, tid, it * 4, dtype);
+        for (int it = 0; it < N / 4; ++it) {
+            const int i0 = index_of<N, SEQ>(base, tid, it * 4, dtype);
             if (i0 + 4 <= vocab) {
                 const float4 w = *reinterpret_cast<const float4 *>(static_cast<const float *>(row) + i0);
                 x[it * 4] = w.x; x[it * 4 + 1] = w.y; x[it * 4 + 2] = w.z; x[it * 4 + 3] = w.w;
@@ -138,41 +143,57 @@ __device__ __forceinline__ T block_sum(T v, T *sh)
     return (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
-// request owning target row r / draft row j (q_indptr[b] - b is the draft-row start of b)
-__device__ __forceinline__ int request_of_row(const int32_t *q_indptr, int batch, int r, bool draft)
-{
-    int lo = 0, hi = batch;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        const int start = q_indptr[mid] - (draft ? mid : 0);
-        if (start <= r) lo = mid; else hi = mid;
+// ---- fp64 exponential for non-positive arguments -----------------------------------------------
+// exp(x) = 2^e * 2^(j/64) * exp(r), x = (64 e + j) ln2/64 + r, |r| <= ln2/128, with a 64-entry
+// table of 2^(j/64) in LDS and a degree-5 Taylor polynomial (remainder < 4e-17 relative).
+struct ExpTable {
+    double t[64];
+    __device__ void init()
+    {
+        if (threadIdx.x < 64) t[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
+        __syncthreads();
     }
-    return lo;
-}
+    __device__ __forceinline__ double operator()(double x) const
+    {
+        if (!(x > -745.0)) return 0.0;  // underflow (also -inf)
+        const double kd = rint(x * 92.33248261689366);  // 64 / ln 2
+        double r = fma(kd, -0x1.62e42fee00000p-7, x);    // ln2/64: high part with 21 trailing zero bits
+        r = fma(kd, -0x1.a39ef35793c76p-39, r);          //         low part
+        const int k = (int)kd;
+        const double p = fma(fma(fma(fma(fma(r, 1.0 / 120.0, 1.0 / 24.0), r, 1.0 / 6.0), r, 0.5), r, 1.0), r, 1.0);
+        return ldexp(t[k & 63] * p, k >> 6);
+    }
+};
 
 // ---- pass 1 ---------------------------------------------------------------------------------
+// grid: batch * kMaxRows * nchunks; workgroup (b, j, chunk) handles chunk `chunk` of request b's row j
+// (j <= k: target row j; k < j <= 2k: draft row j-k-1; larger j: nothing to do).
 __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ float sh[4];
     __shared__ int shi[4];
-    const int chunk = blockIdx.x % w.nchunks, ry = blockIdx.x / w.nchunks, tid = threadIdx.x;
-    const bool is_draft = ry >= a.total_rows;
-    const int r = is_draft ? ry - a.total_rows : ry;
+    const int chunk = blockIdx.x % w.nchunks, tid = threadIdx.x;
+    const int bj = blockIdx.x / w.nchunks, b = bj / kMaxRows, j = bj % kMaxRows;
+    const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1;
+    if (j > (a.greedy ? k : 2 * k)) return;
+    const bool is_draft = j > k;
+    const int r = is_draft ? t0 - b + (j - k - 1) : t0 + j;
+    const int64_t ry = is_draft ? (int64_t)a.total_rows + r : r;
     const void *row = row_ptr(is_draft ? a.draft : a.target, r, a.row_stride, a.logit_dtype);
     float x[kPerThread];
-    load_slots<false>(row, a.vocab, chunk * kChunk, tid, a.logit_dtype, x);
+    load_slots<kPerThread, false>(row, a.vocab, chunk * kChunk, tid, a.logit_dtype, x);
 
     float m = x[0];
 #pragma unroll
     for (int s = 1; s < kPerThread; ++s) m = fmaxf(m, x[s]);
-    const float cm = block_max(m, sh);
-    const int64_t o = (int64_t)ry * w.nchunks + chunk;
+    const int64_t o = ry * w.nchunks + chunk;
     if (a.greedy) {
+        const float cm = block_max(m, sh);
         // lowest vocabulary id holding the chunk maximum
         int best = 0x7fffffff;
 #pragma unroll
         for (int s = 0; s < kPerThread; ++s) {
-            const int id = index_of<false>(chunk * kChunk, tid, s, a.logit_dtype);
+            const int id = index_of<kPerThread, false>(chunk * kChunk, tid, s, a.logit_dtype);
             if (x[s] == cm && id < best) best = id;
         }
         for (int off = 32; off; off >>= 1) best = min(best, __shfl_xor(best, off));
@@ -185,14 +206,17 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
         }
         return;
     }
-    float T = a.temperature_scalar;
-    if (a.temperature) T = a.temperature[request_of_row(a.q_indptr, a.batch, r, is_draft)];
+    // each lane sums its exponentials against its own maximum first (no barrier before the
+    // transcendental work), the 256 (max, sum) pairs are combined afterwards
+    const float T = a.temperature ? a.temperature[b] : a.temperature_scalar;
     const float sc = 1.4426950408889634f / T;
     float z = 0.f;
-    if (cm != -INFINITY) {
+    if (m != -INFINITY) {
 #pragma unroll
-        for (int s = 0; s < kPerThread; ++s) z += exp2f((x[s] - cm) * sc);
+        for (int s = 0; s < kPerThread; ++s) z += __builtin_amdgcn_exp2f((x[s] - m) * sc);
     }
+    const float cm = block_max(m, sh);
+    if (m != -INFINITY) z *= __builtin_amdgcn_exp2f((m - cm) * sc);
     z = block_sum<float>(z, sh);
     if (tid == 0) {
         w.cmax[o] = cm;
@@ -201,19 +225,21 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
 }
 
 // ---- decide ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void accept_decide_kernel(AcceptArgs a, Workspace w)
+// One 256-lane workgroup per request.  Wave wv merges the chunk statistics of rows wv, wv+4, ...
+// (lanes over chunks), then lanes 0..k-1 of wave 0 evaluate their draft and a ballot finds the
+// first rejection.
+__global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, Workspace w)
 {
-    __shared__ float row_m[2 * SS_OUT_WIDTH];
-    __shared__ double row_z[2 * SS_OUT_WIDTH];
-    __shared__ int row_arg[SS_OUT_WIDTH];
-    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ float row_m[kMaxRows];
+    __shared__ double row_z[kMaxRows];
+    __shared__ int row_arg[kMaxRows];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1, d0 = t0 - b;
     const float T = a.temperature ? a.temperature[b] : a.temperature_scalar;
     const double inv_t = a.greedy ? 1.0 : 1.0 / (double)T;
-
-    // merge chunk statistics of the k+1 target rows and k draft rows
     const int nrows = a.greedy ? k + 1 : 2 * k + 1;
-    for (int j = 0; j < nrows; ++j) {
+
+    for (int j = wave; j < nrows; j += 4) {
         const int64_t ry = j <= k ? (int64_t)t0 + j : (int64_t)a.total_rows + d0 + (j - k - 1);
         float m = -INFINITY;
         for (int c = lane; c < w.nchunks; c += 64) m = fmaxf(m, w.cmax[ry * w.nchunks + c]);
@@ -239,106 +265,120 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(AcceptArgs a, Workspa
         }
     }
     __syncthreads();
-    if (lane != 0) return;
+    if (wave != 0) return;
 
-    int32_t *toks = a.out_tokens + (int64_t)b * SS_OUT_WIDTH;
-    int n = k;
-    if (a.greedy) {
-        n = 0;
-        while (n < k && row_arg[n] == a.draft_tokens[d0 + n]) ++n;
-    } else {
-        for (int i = 0; i < k; ++i) {
-            const int x = a.draft_tokens[d0 + i];
-            const double lp = load_logit(a.target, t0 + i, a.row_stride, a.logit_dtype, x);
-            const double lq = load_logit(a.draft, d0 + i, a.row_stride, a.logit_dtype, x);
+    // every draft in parallel: lane i judges draft i
+    bool reject = false;
+    int x = -1;
+    if (lane < k) {
+        x = a.draft_tokens[d0 + lane];
+        if (a.greedy) {
+            reject = row_arg[lane] != x;
+        } else {
+            const double lp = load_logit(a.target, t0 + lane, a.row_stride, a.logit_dtype, x);
+            const double lq = load_logit(a.draft, d0 + lane, a.row_stride, a.logit_dtype, x);
             // p(x)/q(x) = exp((lp-mp)/T - (lq-mq)/T) * Zq/Zp
-            const double e = (lp - (double)row_m[i]) * inv_t - (lq - (double)row_m[k + 1 + i]) * inv_t;
-            const double rho = exp(e) * (row_z[k + 1 + i] / row_z[i]);
-            if (a.ratio_out) a.ratio_out[d0 + i] = (float)rho;
-            if (n == k && !((double)a.u_accept[d0 + i] < rho)) n = i;
+            const double e = (lp - (double)row_m[lane]) * inv_t - (lq - (double)row_m[k + 1 + lane]) * inv_t;
+            const double rho = exp(e) * (row_z[k + 1 + lane] / row_z[lane]);
+            if (a.ratio_out) a.ratio_out[d0 + lane] = (float)rho;
+            reject = !((double)a.u_accept[d0 + lane] < rho);
         }
     }
-    for (int j = 0; j < SS_OUT_WIDTH; ++j) toks[j] = j < n ? a.draft_tokens[d0 + j] : -1;
-    a.accepted_len[b] = n;
-    if (a.greedy) {
-        toks[n] = row_arg[n];
-        return;
+    const unsigned long long rej = __ballot(reject);
+    const int n = rej ? __ffsll((long long)rej) - 1 : k;   // first rejection, k if none
+    if (lane < SS_OUT_WIDTH) {
+        int tok = lane < n ? x : -1;
+        if (a.greedy && lane == n) tok = row_arg[n];
+        a.out_tokens[(int64_t)b * SS_OUT_WIDTH + lane] = tok;   // slot n is filled by pass 2c when sampling
     }
-    RowPick pk;
-    pk.p_row = t0 + n;
-    pk.q_row = n < k ? d0 + n : -1;
-    pk.m_p = row_m[n];
-    pk.m_q = n < k ? row_m[k + 1 + n] : 0.f;
-    pk.temperature = T;
-    pk.n = n;
-    pk.pad[0] = pk.pad[1] = 0;
-    w.pick[b] = pk;
+    if (lane == 0) {
+        a.accepted_len[b] = n;
+        if (!a.greedy) {
+            RowPick pk;
+            pk.p_row = t0 + n;
+            pk.q_row = n < k ? d0 + n : -1;
+            pk.m_p = row_m[n];
+            pk.m_q = n < k ? row_m[k + 1 + n] : 0.f;
+            pk.temperature = T;
+            pk.n = n;
+            pk.pad[0] = pk.pad[1] = 0;
+            w.pick[b] = pk;
+        }
+    }
 }
 
-// ---- pass 2a: fp64 normalisers per chunk ---------------------------------------------------
+// ---- pass 2a: fp64 normalisers per block ----------------------------------------------------
 __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
-    const int chunk = blockIdx.x % w.nchunks, b = blockIdx.x / w.nchunks, tid = threadIdx.x;
+    __shared__ ExpTable ex;
+    ex.init();
+    const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
     const RowPick pk = w.pick[b];
     const double inv_t = 1.0 / (double)pk.temperature;
-    float x[kPerThread];
-    load_slots<false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, chunk * kChunk, tid,
-                      a.logit_dtype, x);
+    float xp[kSubPer], xq[kSubPer];
+    load_slots<kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
+                               a.logit_dtype, xp);
+    if (pk.q_row >= 0)
+        load_slots<kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
+                                   a.logit_dtype, xq);
     double z = 0.0;
-#pragma unroll 4
-    for (int s = 0; s < kPerThread; ++s) z += exp(((double)x[s] - (double)pk.m_p) * inv_t);
+#pragma unroll
+    for (int s = 0; s < kSubPer; ++s) z += ex(((double)xp[s] - (double)pk.m_p) * inv_t);
     z = block_sum<double>(z, sh);
-    if (tid == 0) w.zp[(int64_t)b * w.nchunks + chunk] = z;
+    if (tid == 0) w.zp[(int64_t)b * w.nsub + sub] = z;
     if (pk.q_row < 0) return;
-    load_slots<false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, chunk * kChunk, tid,
-                      a.logit_dtype, x);
     z = 0.0;
-#pragma unroll 4
-    for (int s = 0; s < kPerThread; ++s) z += exp(((double)x[s] - (double)pk.m_q) * inv_t);
+#pragma unroll
+    for (int s = 0; s < kSubPer; ++s) z += ex(((double)xq[s] - (double)pk.m_q) * inv_t);
     z = block_sum<double>(z, sh);
-    if (tid == 0) w.zq[(int64_t)b * w.nchunks + chunk] = z;
+    if (tid == 0) w.zq[(int64_t)b * w.nsub + sub] = z;
 }
 
-__device__ __forceinline__ double ordered_total(const double *v, int n)
+// Sum of v[0..n) with a fixed association (lane-strided partial sums, then the block tree): every
+// workgroup that calls it on the same array gets the same bits.
+__device__ __forceinline__ double block_total(const double *v, int n, double *sh)
 {
     double s = 0.0;
-    for (int c = 0; c < n; ++c) s += v[c];
-    return s;
+    for (int c = threadIdx.x; c < n; c += kThreads) s += v[c];
+    return block_sum<double>(s, sh);
 }
 
 // residual (or bonus) mass of one vocabulary entry
-__device__ __forceinline__ double mass(float lp, float lq, const RowPick &pk, double inv_t, double inv_zp, double inv_zq)
+__device__ __forceinline__ double mass(const ExpTable &ex, float lp, float lq, const RowPick &pk, double inv_t,
+                                       double inv_zp, double inv_zq)
 {
-    const double p = exp(((double)lp - (double)pk.m_p) * inv_t) * inv_zp;
+    const double p = ex(((double)lp - (double)pk.m_p) * inv_t) * inv_zp;
     if (pk.q_row < 0) return p;
-    const double q = exp(((double)lq - (double)pk.m_q) * inv_t) * inv_zq;
+    const double q = ex(((double)lq - (double)pk.m_q) * inv_t) * inv_zq;
     return p > q ? p - q : 0.0;
 }
 
-// ---- pass 2b: residual mass per chunk -------------------------------------------------------
+// ---- pass 2b: residual mass per block -------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void accept_mass_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
-    const int chunk = blockIdx.x % w.nchunks, b = blockIdx.x / w.nchunks, tid = threadIdx.x;
+    __shared__ ExpTable ex;
+    const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
     const RowPick pk = w.pick[b];
-    const double zp = ordered_total(w.zp + (int64_t)b * w.nchunks, w.nchunks);
-    if (pk.q_row < 0) {  // bonus distribution: the chunk's share of p
-        if (tid == 0) w.sc[(int64_t)b * w.nchunks + chunk] = w.zp[(int64_t)b * w.nchunks + chunk] / zp;
+    const double zp = block_total(w.zp + (int64_t)b * w.nsub, w.nsub, sh);
+    if (pk.q_row < 0) {  // bonus distribution: the block's share of p
+        if (tid == 0) w.sc[(int64_t)b * w.nsub + sub] = w.zp[(int64_t)b * w.nsub + sub] / zp;
         return;
     }
-    const double zq = ordered_total(w.zq + (int64_t)b * w.nchunks, w.nchunks);
+    ex.init();
+    float xp[kSubPer], xq[kSubPer];
+    load_slots<kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
+                               a.logit_dtype, xp);
+    load_slots<kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
+                               a.logit_dtype, xq);
+    const double zq = block_total(w.zq + (int64_t)b * w.nsub, w.nsub, sh);
     const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
-    float xp[kPerThread], xq[kPerThread];
-    load_slots<false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, chunk * kChunk, tid,
-                      a.logit_dtype, xp);
-    load_slots<false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, chunk * kChunk, tid,
-                      a.logit_dtype, xq);
     double s = 0.0;
-#pragma unroll 4
-    for (int i = 0; i < kPerThread; ++i) s += mass(xp[i], xq[i], pk, inv_t, inv_zp, inv_zq);
+#pragma unroll
+    for (int i = 0; i < kSubPer; ++i) s += mass(ex, xp[i], xq[i], pk, inv_t, inv_zp, inv_zq);
     s = block_sum<double>(s, sh);
-    if (tid == 0) w.sc[(int64_t)b * w.nchunks + chunk] = s;
+    if (tid == 0) w.sc[(int64_t)b * w.nsub + sub] = s;
 }
 
 // ---- pass 2c: inverse-CDF search ------------------------------------------------------------
@@ -347,16 +387,53 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     __shared__ double wave_tot[4];
     __shared__ int sh_first[4], sh_last[4];
     __shared__ float sh_f[4];
+    __shared__ ExpTable ex;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowPick pk = w.pick[b];
     int32_t *dst = a.out_tokens + (int64_t)b * SS_OUT_WIDTH + pk.n;
-    const double *sc = w.sc + (int64_t)b * w.nchunks;
+    const double *sc = w.sc + (int64_t)b * w.nsub;
 
-    // chunk that holds u * S (every lane does the same short scan)
-    const double S = ordered_total(sc, w.nchunks);
+    // Inclusive scan of the block masses in index order (lane c holds block c; vocabularies beyond
+    // 256 blocks take several rounds), first for the total S, then again to find the first block
+    // with mass whose running sum exceeds u * S, together with the mass in front of it.
+    __shared__ double scan_tot[4];
+    __shared__ double carry_sh, prefix_sh;
+    __shared__ int cstar_sh, lastpos_sh;
+    double S = 0.0;
+    int cand = 0x7fffffff, last = -1;
+    double cand_prefix = 0.0, last_prefix = 0.0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const double thr0 = (double)a.u_sample[b] * S;
+        __syncthreads();
+        if (tid == 0) { carry_sh = 0.0; cstar_sh = 0x7fffffff; lastpos_sh = -1; }
+        __syncthreads();
+        for (int base = 0; base < w.nsub; base += kThreads) {
+            const int c = base + tid;
+            const double v = c < w.nsub ? sc[c] : 0.0;
+            double incl = v;
+            for (int off = 1; off < 64; off <<= 1) {
+                const double t = __shfl_up(incl, off);
+                if (lane >= off) incl += t;
+            }
+            if (lane == 63) scan_tot[wave] = incl;
+            __syncthreads();
+            double before = carry_sh;
+            for (int wv = 0; wv < wave; ++wv) before += scan_tot[wv];
+            const double cum = before + incl;   // running sum through block c
+            if (pass == 1 && v > 0.0) {
+                if (cum > thr0 && c < cand) { cand = c; cand_prefix = cum - v; }
+                last = c;
+                last_prefix = cum - v;
+            }
+            __syncthreads();
+            if (tid == kThreads - 1) carry_sh = cum;
+            __syncthreads();
+        }
+        if (pass == 0) S = carry_sh;
+        if (!(S > 0.0)) break;
+    }
     if (!(S > 0.0)) {
         // p_n == q_n exactly: no residual mass; fall back to the lowest-index argmax of the target row
-        const void *row = row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype);
         float best = -INFINITY;
         for (int v = tid; v < a.vocab; v += kThreads)
             best = fmaxf(best, load_logit(a.target, pk.p_row, a.row_stride, a.logit_dtype, v));
@@ -368,46 +445,40 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
         if (lane == 0) sh_first[wave] = arg;
         __syncthreads();
         if (tid == 0) *dst = min(min(sh_first[0], sh_first[1]), min(sh_first[2], sh_first[3]));
-        (void)row;
         return;
     }
+    atomicMin(&cstar_sh, cand);
+    atomicMax(&lastpos_sh, last);
+    __syncthreads();
+    const bool take_last = cstar_sh == 0x7fffffff;  // rounding left u*S at or past the total: last entry with mass
+    const int cstar = take_last ? lastpos_sh : cstar_sh;
+    if (!take_last && cand == cstar) prefix_sh = cand_prefix;
+    if (take_last && last == cstar) prefix_sh = last_prefix;
+    ex.init();   // (contains the barrier that publishes prefix_sh)
     const double thr = (double)a.u_sample[b] * S;
-    int cstar = -1, last_pos = -1;
-    double prefix = 0.0, run = 0.0;
-    for (int c = 0; c < w.nchunks; ++c) {
-        if (sc[c] > 0.0) {
-            last_pos = c;
-            if (cstar < 0 && run + sc[c] > thr) {
-                cstar = c;
-                prefix = run;
-            }
-            run += sc[c];
-        }
-    }
-    const bool take_last = cstar < 0;  // rounding left u*S at or past the total: last entry with mass
-    if (take_last) cstar = last_pos;
+    const double prefix = prefix_sh;
 
-    const double zp = ordered_total(w.zp + (int64_t)b * w.nchunks, w.nchunks);
-    const double zq = pk.q_row >= 0 ? ordered_total(w.zq + (int64_t)b * w.nchunks, w.nchunks) : 1.0;
+    const double zp = block_total(w.zp + (int64_t)b * w.nsub, w.nsub, wave_tot);
+    const double zq = pk.q_row >= 0 ? block_total(w.zq + (int64_t)b * w.nsub, w.nsub, wave_tot) : 1.0;
     const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
-    float xp[kPerThread], xq[kPerThread];
-    load_slots<true>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kChunk, tid,
-                     a.logit_dtype, xp);
+    float xp[kSubPer], xq[kSubPer];
+    load_slots<kSubPer, true>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kSub, tid,
+                              a.logit_dtype, xp);
     if (pk.q_row >= 0)
-        load_slots<true>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kChunk, tid,
-                         a.logit_dtype, xq);
+        load_slots<kSubPer, true>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kSub, tid,
+                                  a.logit_dtype, xq);
     else {
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) xq[i] = 0.f;
+        for (int i = 0; i < kSubPer; ++i) xq[i] = 0.f;
     }
-    double r[kPerThread];
+    double r[kSubPer];
     double local = 0.0;
     int my_last = -1;
-#pragma unroll 4
-    for (int i = 0; i < kPerThread; ++i) {
-        r[i] = mass(xp[i], xq[i], pk, inv_t, inv_zp, inv_zq);
+#pragma unroll
+    for (int i = 0; i < kSubPer; ++i) {
+        r[i] = mass(ex, xp[i], xq[i], pk, inv_t, inv_zp, inv_zq);
         local += r[i];
-        if (r[i] > 0.0) my_last = cstar * kChunk + tid * kPerThread + i;
+        if (r[i] > 0.0) my_last = cstar * kSub + tid * kSubPer + i;
     }
     // exclusive prefix of `local` over lanes in index order
     double incl = local;
@@ -437,11 +508,11 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     if (tid == first) {
         double c = excl;
         int tok = -1;
-#pragma unroll 4
-        for (int i = 0; i < kPerThread; ++i) {
+#pragma unroll
+        for (int i = 0; i < kSubPer; ++i) {
             if (r[i] > 0.0) {
                 c += r[i];
-                if (tok < 0 && c > thr) tok = cstar * kChunk + tid * kPerThread + i;
+                if (tok < 0 && c > thr) tok = cstar * kSub + tid * kSubPer + i;
             }
         }
         // the lane total crossed but the element-wise sum may round differently: then its last entry with mass
@@ -453,26 +524,29 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
 
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab)
 {
-    const size_t nch = num_chunks(vocab);
+    const size_t nch = num_chunks(vocab), nsub = num_sub(vocab);
     const size_t rows = 2 * (size_t)total_rows - batch;
     size_t n = 3 * align_up(sizeof(float) * rows * nch, 256);
     n += align_up(sizeof(RowPick) * (size_t)batch, 256);
-    n += 3 * align_up(sizeof(double) * (size_t)batch * nch, 256);
+    n += 3 * align_up(sizeof(double) * (size_t)batch * nsub, 256);
     return n + 256;
 }
 
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
 {
     const Workspace w = carve(a.workspace, a.batch, a.total_rows, a.vocab);
-    const unsigned rows = a.greedy ? (unsigned)a.total_rows : (unsigned)w.rows;
-    hipLaunchKernelGGL(accept_rowstats_kernel, dim3((unsigned)w.nchunks * rows), dim3(kThreads), 0, stream, a, w);
+    const unsigned long long g1 = (unsigned long long)a.batch * kMaxRows * w.nchunks;
+    const unsigned long long g2 = (unsigned long long)a.batch * w.nsub;
+    if (g1 > 0x7fffffffull || g2 > 0x7fffffffull)
+        return fail(SS_ERR_UNSUPPORTED, "batch * vocab too large for one launch");
+    hipLaunchKernelGGL(accept_rowstats_kernel, dim3((unsigned)g1), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(a.batch), dim3(64), 0, stream, a, w);
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_decide_kernel");
     if (a.greedy) return SS_OK;
-    hipLaunchKernelGGL(accept_norm_kernel, dim3((unsigned)w.nchunks * (unsigned)a.batch), dim3(kThreads), 0, stream, a, w);
+    hipLaunchKernelGGL(accept_norm_kernel, dim3((unsigned)g2), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_norm_kernel");
-    hipLaunchKernelGGL(accept_mass_kernel, dim3((unsigned)w.nchunks * (unsigned)a.batch), dim3(kThreads), 0, stream, a, w);
+    hipLaunchKernelGGL(accept_mass_kernel, dim3((unsigned)g2), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_mass_kernel");
     hipLaunchKernelGGL(accept_pick_kernel, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_pick_kernel");

@@ -411,13 +411,20 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// merge: one workgroup per unit
+// merge: workgroup (unit, slab) combines the partials of 8 query rows of one unit
 // ---------------------------------------------------------------------------------------------
+constexpr int kMergeRows = 8;
+
 template <int G>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 {
-    const int unit = blockIdx.x;
+    const int slabs = a.rows_pad / kMergeRows;
+    const int unit = blockIdx.x / slabs, slab = blockIdx.x % slabs;
     const int b = unit / a.num_kv_heads, g = unit % a.num_kv_heads;
+    const int q0 = a.q_indptr[b];
+    const int rows = (a.q_indptr[b + 1] - q0) * G;
+    const int n = slab * kMergeRows + (threadIdx.x >> 5), d4 = threadIdx.x & 31;
+    if (n >= rows) return;
     const long long total = a.plan->total_tiles;
     const long long nw = a.plan->num_waves;
     const int pre = a.tile_prefix[b];
@@ -427,41 +434,30 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     // is ((t+1)*nw - 1) / total
     const int w_first = (int)(((off + 1) * nw - 1) / total);
     const int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
-    const int q0 = a.q_indptr[b];
-    const int q_len = a.q_indptr[b + 1] - q0;
-    const int rows = q_len * G;
 
-    for (int item = threadIdx.x; item < rows * (D / 4); item += 256) {
-        const int n = item / (D / 4), d4 = item % (D / 4);
-        float m_all = -INFINITY;
-        for (int w = w_first; w <= w_last; ++w) {
-            const long long slot = (long long)w + unit;
-            m_all = fmaxf(m_all, a.part_ml[(slot * a.rows_pad + n) * 2]);
-        }
-        float l_all = 0.f;
-        float4v o = {0.f, 0.f, 0.f, 0.f};
-        for (int w = w_first; w <= w_last; ++w) {
-            const long long slot = (long long)w + unit;
-            const float mp = a.part_ml[(slot * a.rows_pad + n) * 2];
-            const float lp = a.part_ml[(slot * a.rows_pad + n) * 2 + 1];
-            const float wgt = exp2f(mp - m_all);  // a partial that saw no visible token has m = -1e30, l = 0
-            l_all += wgt * lp;
-            if (wgt != 0.f) {
-                const float4v op = *reinterpret_cast<const float4v *>(a.part_o + (slot * a.rows_pad + n) * D + d4 * 4);
-                o += op * wgt;
-            }
-        }
-        const float inv = 1.f / l_all;
-        const int qi = n / G, hh = n % G;
-        const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
-        __bf16 *dst = static_cast<__bf16 *>(a.out) + orow * D + d4 * 4;
-        uint2 pk;
-        const __bf16 b0 = (__bf16)(o.x * inv), b1 = (__bf16)(o.y * inv), b2 = (__bf16)(o.z * inv), b3 = (__bf16)(o.w * inv);
-        pk.x = (uint32_t)__builtin_bit_cast(uint16_t, b0) | ((uint32_t)__builtin_bit_cast(uint16_t, b1) << 16);
-        pk.y = (uint32_t)__builtin_bit_cast(uint16_t, b2) | ((uint32_t)__builtin_bit_cast(uint16_t, b3) << 16);
-        *reinterpret_cast<uint2 *>(dst) = pk;
-        if (a.lse && d4 == 0) a.lse[orow] = (m_all + log2f(l_all)) * kLn2;
+    // running merge: (m, l, o) <- (m, l, o) (+) partial, both relative to their own reference m
+    float m_all = kNoMax, l_all = 0.f;
+    float4v o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int w = w_first; w <= w_last; ++w) {
+        const long long row = ((long long)w + unit) * a.rows_pad + n;
+        const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + row * 2);
+        const float4v op = *reinterpret_cast<const float4v *>(a.part_o + row * D + d4 * 4);
+        const float m_new = fmaxf(m_all, ml.x);
+        const float wa = exp2f(m_all - m_new), wb = exp2f(ml.x - m_new);  // a partial without visible tokens has l = 0
+        l_all = l_all * wa + ml.y * wb;
+        o = o * wa + op * wb;
+        m_all = m_new;
     }
+    const float inv = 1.f / l_all;
+    const int qi = n / G, hh = n % G;
+    const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
+    const float2v lo = {o.x * inv, o.y * inv}, hi = {o.z * inv, o.w * inv};
+    uint2 pk;
+    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+    *reinterpret_cast<uint2 *>(static_cast<__bf16 *>(a.out) + orow * D + d4 * 4) = pk;
+    if (a.lse && d4 == 0) a.lse[orow] = (m_all + log2f(l_all)) * kLn2;
 }
 
 template <int G, int NB, bool FP8>
@@ -483,7 +479,8 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
                        b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
     if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
-    hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
+    hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads * (a.rows_pad / kMergeRows)), dim3(256),
+                       0, stream, b);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_merge_kernel");
     return SS_OK;
 }
