@@ -54,6 +54,9 @@ static int32_t check_attn_shape(const ss_paged_kv *kv, const ss_batch *b, int32_
     if (b->batch > 0 && b->max_blocks_per_seq <= 0)
         return fail(SS_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
     if (kv->num_blocks < 0) return fail(SS_ERR_INVALID_ARG, "negative num_blocks");
+    if ((int64_t)kv->num_blocks * kv->num_kv_heads > 0x7fffffffll ||
+        (int64_t)b->batch * b->max_blocks_per_seq * kv->num_kv_heads > 0x7fffffffll)
+        return fail(SS_ERR_UNSUPPORTED, "num_blocks * num_kv_heads and batch * max_blocks * num_kv_heads must fit 31 bits");
     if (b->max_q_len < 0 || b->max_q_len > SS_OUT_WIDTH || b->reserved != 0)
         return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d], reserved must be 0", SS_OUT_WIDTH);
     return SS_OK;
@@ -103,7 +106,8 @@ size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batc
                                      int32_t total_rows)
 {
     if (check_attn_shape(kv, batch, num_q_heads, total_rows) != SS_OK) return 0;
-    return attn_workspace_bytes(batch->batch, num_q_heads, kv->num_kv_heads, kv->head_dim, attn_default_waves());
+    return attn_workspace_bytes(batch->batch, batch->max_blocks_per_seq, num_q_heads, kv->num_kv_heads, kv->head_dim,
+                                attn_default_waves());
 }
 
 int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,
@@ -122,7 +126,8 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
         return fail(SS_ERR_INVALID_ARG, "k, v, q and out must be 16-byte aligned");
     if (!(sm_scale == sm_scale) || sm_scale <= 0.0f) return fail(SS_ERR_INVALID_ARG, "sm_scale must be positive");
     const int launch_waves = attn_default_waves();
-    const size_t need = attn_workspace_bytes(batch->batch, num_q_heads, kv->num_kv_heads, kv->head_dim, launch_waves);
+    const size_t need = attn_workspace_bytes(batch->batch, batch->max_blocks_per_seq, num_q_heads, kv->num_kv_heads,
+                                             kv->head_dim, launch_waves);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
     if (workspace_bytes < need)
@@ -145,6 +150,8 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     w += 256;
     a.tile_prefix = reinterpret_cast<int32_t *>(w);
     w += align_up(sizeof(int32_t) * ((size_t)batch->batch + 1), 256);
+    a.tile_addr = reinterpret_cast<int32_t *>(w);
+    w += align_up(sizeof(int32_t) * (size_t)batch->batch * batch->max_blocks_per_seq * kv->num_kv_heads, 256);
     const size_t slots = (size_t)launch_waves + (size_t)batch->batch * kv->num_kv_heads;
     a.part_ml = reinterpret_cast<float *>(w);
     w += align_up(slots * a.rows_pad * 2 * sizeof(float), 256);

@@ -2,12 +2,14 @@
 //
 // Work decomposition.  The KV cache of one (request, KV head) pair ("unit") is a run of
 // 16-token tiles, one per cache block.  All tiles of all units form one flat sequence (unit
-// major); it is cut into `num_waves` equal contiguous spans and every wavefront streams one
-// span, so the load is balanced whatever the mix of context lengths.  A span may cover the
-// tail of one unit, several whole units and the head of another; for every unit it touches
-// the wave emits one partial result (running max, sum, unnormalised output) into slot
-// `wave + unit` (that sum is unique along the sequence).  A second kernel merges the partials
-// of each unit by their log-sum-exp and writes the rounded output.
+// major).  A plan kernel writes that sequence out as a flat list of tile addresses (physical
+// block * kv heads + kv head) and cuts it into `num_waves` equal contiguous spans; every
+// wavefront streams one span, so the load is balanced whatever the mix of context lengths, and
+// the load side of the kernel is a plain linear walk that never stops at a unit boundary.  A
+// span may cover the tail of one unit, several whole units and the head of another; for every
+// unit it touches the wave emits one partial result (softmax reference, sum, unnormalised
+// output) into slot `wave + unit` (that sum is unique along the sequence).  A last kernel
+// merges the partials of each unit by their log-sum-exp and writes the rounded output.
 //
 // Per tile, with rows = (k+1) * (query heads per KV head) padded to a multiple of 16:
 //   S^T[token][row] = K[token][:] . Q[row][:]   v_mfma_f32_16x16x32_bf16, K tile as A operand
@@ -36,43 +38,39 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
 constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
+constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
 
 // ---------------------------------------------------------------------------------------------
-// plan: tile prefix over requests, total tiles, number of partitions
+// plan: workgroup (b, g) sums the tile counts of the requests in front of b, writes the flat tile
+// address list of its unit, and (b, 0) / the last one publish the prefix and the partition count
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
 {
-    __shared__ int wsum[4];
-    __shared__ int carry_s;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry_s = 0;
+    __shared__ int sh[4];
+    const int b = blockIdx.x / a.num_kv_heads, g = blockIdx.x % a.num_kv_heads;
+    const int tid = threadIdx.x;
+    int part = 0;
+    for (int i = tid; i < b; i += 256) part += (a.kv_len[i] + kTile - 1) / kTile;
+    for (int off = 32; off; off >>= 1) part += __shfl_xor(part, off);
+    if ((tid & 63) == 0) sh[tid >> 6] = part;
     __syncthreads();
-    for (int base = 0; base < a.batch; base += 256) {
-        const int b = base + tid;
-        const int n = b < a.batch ? (a.kv_len[b] + kTile - 1) / kTile : 0;
-        int incl = n;  // inclusive scan inside the wave
-        for (int off = 1; off < 64; off <<= 1) {
-            int t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
+    const int pre = sh[0] + sh[1] + sh[2] + sh[3];
+    const int n = (a.kv_len[b] + kTile - 1) / kTile;
+    const int32_t *bt = a.block_table + (long long)b * a.max_blocks;
+    int32_t *dst = a.tile_addr + (long long)pre * a.num_kv_heads + (long long)g * n;
+    for (int t = tid; t < n; t += 256) dst[t] = bt[t] * a.num_kv_heads + g;
+    if (g == 0 && tid == 0) {
+        a.tile_prefix[b] = pre;
+        if (b == a.batch - 1) {
+            const int per_head = pre + n;
+            a.tile_prefix[a.batch] = per_head;
+            const long long total = (long long)per_head * a.num_kv_heads;
+            long long nw = total / kMinTilesPerWave;
+            if (nw < 1) nw = 1;
+            if (nw > a.launch_waves) nw = a.launch_waves;
+            a.plan->total_tiles = (int)total;
+            a.plan->num_waves = (int)nw;
         }
-        if (lane == 63) wsum[wave] = incl;
-        __syncthreads();
-        int before = carry_s;
-        for (int w = 0; w < wave; ++w) before += wsum[w];
-        if (b < a.batch) a.tile_prefix[b] = before + incl - n;
-        __syncthreads();
-        if (tid == 255) carry_s = before + incl;
-        __syncthreads();
-    }
-    if (tid == 0) {
-        const int per_head = carry_s;
-        a.tile_prefix[a.batch] = per_head;
-        const long long total = (long long)per_head * a.num_kv_heads;
-        long long nw = total / kMinTilesPerWave;
-        if (nw < 1) nw = 1;
-        if (nw > a.launch_waves) nw = a.launch_waves;
-        a.plan->total_tiles = (int)total;
-        a.plan->num_waves = (int)nw;
     }
 }
 
@@ -116,14 +114,15 @@ struct TileRegs {
 };
 
 // All loads of one tile are vector loads issued back to back, so one counter orders them and the
-// consumer can wait for exactly this tile.  `vzero` is a lane register holding 0 that the compiler
-// cannot see through: it keeps the (wave-uniform) scale reads on the vector path too.
+// consumer can wait for exactly this tile.  `addr` = physical block * kv heads + kv head indexes
+// both the 4 KB (2 KB for e4m3) tile and its scale.  `vzero` is a lane register holding 0 that the
+// compiler cannot see through: it keeps the (wave-uniform) scale reads on the vector path too.
 template <bool FP8>
 __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, const float *__restrict__ k_scale,
-                                          const float *__restrict__ v_scale, int64_t phys, int g, int lane, int vzero)
+                                          const float *__restrict__ v_scale, int addr, int lane, int vzero)
 {
     constexpr int ES = FP8 ? 1 : 2;
-    const int64_t blk = (phys * a.num_kv_heads + g) * (int64_t)(kTile * D * ES);
+    const int64_t blk = (int64_t)addr * (kTile * D * ES);
     const char *kp = static_cast<const char *>(a.k) + blk + (lane & 15) * (D * ES) + (lane >> 4) * 16;
     const char *vp = static_cast<const char *>(a.v) + blk + (lane >> 4) * (4 * D * ES) + (lane & 15) * (8 * ES);
 #pragma unroll
@@ -136,8 +135,8 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
             t.v[e] = *reinterpret_cast<const uint4 *>(vp + e * (D * ES));
     }
     if constexpr (FP8) {
-        t.ks = k_scale[phys * a.num_kv_heads + g + vzero];
-        t.vs = v_scale[phys * a.num_kv_heads + g + vzero];
+        t.ks = k_scale[addr + vzero];
+        t.vs = v_scale[addr + vzero];
     } else {
         t.ks = 1.f;
         t.vs = 1.f;
@@ -149,55 +148,64 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 // OCC   wavefronts per SIMD the register budget is sized for
 template <int G, int NB, bool FP8, int NBUF, int OCC>
 __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
-    AttnArgs a, const int32_t *__restrict__ block_table, const int32_t *__restrict__ tile_prefix,
+    AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ tile_prefix,
     const int32_t *__restrict__ kv_len, const int32_t *__restrict__ q_indptr, const float *__restrict__ k_scale,
     const float *__restrict__ v_scale)
 {
     // The metadata arrays come in as separate no-alias arguments so that their wave-uniform reads
     // become scalar loads (own counter, no ordering against the vector KV loads).
+    __shared__ int32_t id_lds[kWavesPerWg][kIdWindow];
     const int lane = threadIdx.x & 63;
     const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = blockIdx.x * kWavesPerWg + wslot;
     const int r16 = lane & 15, jq = lane >> 4;
     int vzero;
     asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+    int32_t *ids = id_lds[wslot];
 
     const int num_waves = a.plan->num_waves;
     const long long total = a.plan->total_tiles;
     if (wave >= num_waves) return;
-    long long x = (long long)wave * total / num_waves;             // first tile of this span
-    const long long x_end = (long long)(wave + 1) * total / num_waves;
-    if (x >= x_end) return;
+    const long long x0 = (long long)wave * total / num_waves;      // this wave's span of the flat tile list
+    const long long x1 = (long long)(wave + 1) * total / num_waves;
+    if (x0 >= x1) return;
 
-    // request holding tile x: largest b with Hkv * tile_prefix[b] <= x
-    const long long per_head_x = x / a.num_kv_heads;  // tile_prefix[b] <= x / Hkv  <=>  Hkv*prefix <= x
+    // unit holding tile x0: largest b with Hkv * tile_prefix[b] <= x0
+    const long long per_head_x = x0 / a.num_kv_heads;
     int b = -1;
     for (int base = 0; base <= a.batch; base += 64) {
         const int idx = base + lane;
         const bool le = idx <= a.batch && (long long)tile_prefix[idx] <= per_head_x;
         b += __popcll(__ballot(le));
     }
-    if (b >= a.batch) b = a.batch - 1;  // x < total, so this only guards against bad plans
-    int pre = tile_prefix[b];
-    int nb_tiles = tile_prefix[b + 1] - pre;
-    long long rem = x - (long long)pre * a.num_kv_heads;
-    int g = (int)(rem / nb_tiles);
-    int tile = (int)(rem % nb_tiles);
+    if (b >= a.batch) b = a.batch - 1;  // x0 < total, so this only guards against bad plans
+    int nb_tiles;
+    int g, tile;
+    {
+        const int pre = tile_prefix[b];
+        nb_tiles = tile_prefix[b + 1] - pre;
+        const long long rem = x0 - (long long)pre * a.num_kv_heads;
+        g = (int)(rem / nb_tiles);
+        tile = (int)(rem % nb_tiles);
+    }
 
-    while (x < x_end) {
-        // ---- one unit segment: request b, kv head g, tiles [tile, t1) ----
-        const int left = (int)((x_end - x) < (long long)(nb_tiles - tile) ? (x_end - x) : (nb_tiles - tile));
-        const int t1 = tile + left;
-        const int L = kv_len[b];
-        const int q0 = q_indptr[b];
-        const int q_len = q_indptr[b + 1] - q0;
-        const int rows = q_len * G;
-        const int nbu = (rows + 15) >> 4;
-        const int32_t *__restrict__ bt = block_table + (long long)b * a.max_blocks;
+    // ---- state of the unit being computed ----
+    int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
+    int seg_left = 0;                 // of those, tiles that still belong to the current unit
+    bool fresh = true;                // the next tile starts a unit segment
+    int L = 0, q0 = 0, q_len = 0, rows = 0;
+    bf16x8 qreg[NB][4];               // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
+    int lim[NB];                      // last visible cache position of this lane's row in block nb
+    float m_run[NB], l_run[NB];
+    float4v acc[8][NB];
+    const float sc2 = a.sm_scale * kLog2e;
 
-        // Q as B operand: lane holds row n = 16*nb + r16, 8 consecutive d per k-step
-        bf16x8 qreg[NB][4];
-        int lim[NB];  // last visible cache position of this lane's row in block nb
+    auto begin_unit = [&]() {
+        L = kv_len[b];
+        q0 = q_indptr[b];
+        q_len = q_indptr[b + 1] - q0;
+        rows = q_len * G;
+        seg_left = nb_tiles - tile < span_left ? nb_tiles - tile : span_left;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int n = nb * 16 + r16;
@@ -213,160 +221,25 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
                 if (ok) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
                 qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
             }
-        }
-
-        float m_run[NB], l_run[NB];
-        float4v acc[8][NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
             m_run[nb] = kNoMax;
             l_run[nb] = 0.f;
 #pragma unroll
             for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
         }
-        const float sc2 = a.sm_scale * kLog2e;
+        // Have the queries arrive here, inside the rarely taken branch, so that the steady-state
+        // path never carries a pending load of them.
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+    };
 
-        // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond this
-        // unit's rows hold zero queries; they are computed anyway (cheaper than branching) and never
-        // stored.  The body is straight-line code apart from the rare rescale: masks are selects that
-        // are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
-        // its result: the wait states the hardware needs there are only inserted inside a block.)
-        auto compute = [&](const TileRegs<FP8> &t, int ti) {
-            const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
-            // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
-            // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
-            const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
-            const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
-            short4v vop[8];
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {   // word h of each token's 8 values holds d-phases 2h and 2h+1
-                uint32_t w[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if constexpr (FP8) {
-                        const uint32_t src = (h < 2) ? t.v[e].x : t.v[e].y;   // two e4m3 bytes -> two bf16, exact
-                        const float2v f = (h & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true)
-                                                  : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
-                        w[e] = pack_hi16(__float_as_uint(f.x), __float_as_uint(f.y));
-                    } else {
-                        w[e] = (&t.v[e].x)[h];
-                    }
-                }
-                uint2 lo, hi;
-                lo.x = pack_lo16(w[0], w[1]) & m01;
-                lo.y = pack_lo16(w[2], w[3]) & m23;
-                hi.x = pack_hi16(w[0], w[1]) & m01;
-                hi.y = pack_hi16(w[2], w[3]) & m23;
-                vop[2 * h] = __builtin_bit_cast(short4v, lo);
-                vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
-            }
-
-            bf16x8 kop[4];
-            if constexpr (FP8) {
-                kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
-                kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
-                kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
-                kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
-            }
-            float4v s[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
-
-            // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
-            // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
-            // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
-            const float kscale = sc2 * t.ks;
-            float sv[NB][4];
-            bool trig = false;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                    sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
-                const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-                trig |= lane_mx > m_run[nb] + kSlack;
-            }
-            if (__any(trig)) {
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-                    mx = fmaxf(mx, __shfl_xor(mx, 16));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(m_run[nb], mx);
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-                    l_run[nb] *= alpha;
-#pragma unroll
-                    for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
-                    m_run[nb] = m_new;
-                }
-            }
-            short4v pop[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                float p[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
-                l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-                const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
-                uint2 pk;
-                pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-                pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-                pop[nb] = __builtin_bit_cast(short4v, pk);
-            }
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb], acc[mb][nb], 0, 0, 0);
-        };
-
-        auto issue = [&](TileRegs<FP8> &t, int tt) {
-            load_tile<FP8>(t, a, k_scale, v_scale, (long long)bt[tt], g, lane, vzero);
-        };
-        // Software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers).
-        // The steady-state loop issues its prefetch unconditionally, so the wait before each
-        // compute only covers the tile it needs and NBUF-1 tiles stay in flight; the last few
-        // tiles of a segment (and short segments) run through a conditional epilogue.
-        TileRegs<FP8> buf[NBUF];
-        int ti = tile;
-        if (t1 - tile >= 2 * NBUF - 1) {
-#pragma unroll
-            for (int j = 0; j < NBUF - 1; ++j) issue(buf[j], tile + j);
-            for (; ti + 2 * NBUF - 2 < t1; ti += NBUF) {
-#pragma unroll
-                for (int j = 0; j < NBUF; ++j) {
-                    issue(buf[(j + NBUF - 1) % NBUF], ti + j + NBUF - 1);
-                    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
-                    compute(buf[j], ti + j);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NBUF - 1; ++j)
-                if (tile + j < t1) issue(buf[j], tile + j);
-        }
-        // here buf[j] holds tile ti + j for j < NBUF-1 (as far as such tiles exist)
-#pragma unroll
-        for (int j = 0; j < 2 * NBUF - 2; ++j) {
-            if (ti + j < t1) {
-                if (ti + j + NBUF - 1 < t1) issue(buf[(j + NBUF - 1) % NBUF], ti + j + NBUF - 1);
-                compute(buf[j % NBUF], ti + j);
-            }
-        }
-
-        // ---- partial result of this segment -> slot wave + unit ----
-        // The accumulators were last written by MFMAs in a different basic block: give them the wait
+    auto end_unit = [&]() {
+        // The accumulators were last written by MFMAs in another basic block: give them the wait
         // states a read needs before anything below touches them.
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        const int nbu = (rows + 15) >> 4;
         const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
         float *po = a.part_o + slot * a.rows_pad * D;
         float *pml = a.part_ml + slot * a.rows_pad * 2;
@@ -394,19 +267,175 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
                 }
             }
         }
-
-        // ---- advance to the next unit ----
-        x += left;
+        // next unit
         tile = 0;
         if (++g == a.num_kv_heads) {
             g = 0;
             ++b;
-            if (b < a.batch) {
-                pre = tile_prefix[b];
-                nb_tiles = tile_prefix[b + 1] - pre;
+            if (b < a.batch) nb_tiles = tile_prefix[b + 1] - tile_prefix[b];
+        }
+    };
+
+    // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond this
+    // unit's rows hold zero queries; they are computed anyway (cheaper than branching) and never
+    // stored.  The body is straight-line code apart from the rare rescale: masks are selects that
+    // are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
+    // its result: the wait states the hardware needs there are only inserted inside a block.)
+    auto compute = [&](const TileRegs<FP8> &t, int ti) {
+        const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
+        // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
+        // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
+        const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
+        const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
+        short4v vop[8];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {   // word h of each token's 8 values holds d-phases 2h and 2h+1
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (FP8) {
+                    const uint32_t src = (h < 2) ? t.v[e].x : t.v[e].y;   // two e4m3 bytes -> two bf16, exact
+                    const float2v f = (h & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true)
+                                              : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
+                    w[e] = pack_hi16(__float_as_uint(f.x), __float_as_uint(f.y));
+                } else {
+                    w[e] = (&t.v[e].x)[h];
+                }
+            }
+            uint2 lo, hi;
+            lo.x = pack_lo16(w[0], w[1]) & m01;
+            lo.y = pack_lo16(w[2], w[3]) & m23;
+            hi.x = pack_hi16(w[0], w[1]) & m01;
+            hi.y = pack_hi16(w[2], w[3]) & m23;
+            vop[2 * h] = __builtin_bit_cast(short4v, lo);
+            vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
+        }
+
+        bf16x8 kop[4];
+        if constexpr (FP8) {
+            kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
+            kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
+            kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
+            kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
+        }
+        float4v s[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
+
+        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
+        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
+        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
+        const float kscale = sc2 * t.ks;
+        float sv[NB][4];
+        bool trig = false;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+            const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+            trig |= lane_mx > m_run[nb] + kSlack;
+        }
+        if (__any(trig)) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[nb], mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+                l_run[nb] *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
+                m_run[nb] = m_new;
             }
         }
-        if (b >= a.batch) break;
+        short4v pop[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float p[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
+            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+            uint2 pk;
+            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            pop[nb] = __builtin_bit_cast(short4v, pk);
+        }
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb], acc[mb][nb], 0, 0, 0);
+    };
+
+    // one step of the compute side: open a unit segment if needed, consume a tile, close the segment
+    auto step = [&](const TileRegs<FP8> &t) {
+        if (fresh) {
+            begin_unit();
+            fresh = false;
+        }
+        compute(t, tile);
+        ++tile;
+        --span_left;
+        if (--seg_left == 0) {
+            end_unit();
+            fresh = true;
+        }
+    };
+
+    // ---- load side: a linear walk over the span's tile addresses, staged in LDS a window at a time ----
+    for (long long c0 = x0; c0 < x1; c0 += kIdWindow) {
+        const int n = (int)(x1 - c0 < kIdWindow ? x1 - c0 : kIdWindow);
+        for (int i = lane; i < n; i += 64) ids[i] = tile_addr[c0 + i];
+        int p_load = 0;
+        int id_v = ids[0];   // address of the next tile to load, read from LDS one step ahead of its use
+        auto issue = [&](TileRegs<FP8> &t) {
+            const int addr = __builtin_amdgcn_readfirstlane(id_v);
+            ++p_load;
+            id_v = ids[p_load < n ? p_load : n - 1];
+            load_tile<FP8>(t, a, k_scale, v_scale, addr, lane, vzero);
+        };
+
+        // Software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers).
+        // The steady-state loop issues its prefetch unconditionally, so the wait before each
+        // compute only covers the tile it needs and NBUF-1 tiles stay in flight; the last few
+        // tiles of a window (and short windows) run through a conditional epilogue.
+        TileRegs<FP8> buf[NBUF];
+        int p = 0;
+        if (n >= 2 * NBUF - 1) {
+#pragma unroll
+            for (int j = 0; j < NBUF - 1; ++j) issue(buf[j]);
+            for (; p + 2 * NBUF - 2 < n; p += NBUF) {
+#pragma unroll
+                for (int j = 0; j < NBUF; ++j) {
+                    issue(buf[(j + NBUF - 1) % NBUF]);
+                    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
+                    step(buf[j]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NBUF - 1; ++j)
+                if (j < n) issue(buf[j]);
+        }
+        // here buf[j] holds tile p + j for j < NBUF-1 (as far as such tiles exist)
+#pragma unroll
+        for (int j = 0; j < 2 * NBUF - 2; ++j) {
+            if (p + j < n) {
+                if (p + j + NBUF - 1 < n) issue(buf[(j + NBUF - 1) % NBUF]);
+                step(buf[j % NBUF]);
+            }
+        }
     }
 }
 
@@ -471,11 +500,11 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
     b.launch_waves -= b.launch_waves % kWavesPerWg;
     if (b.launch_waves < kWavesPerWg) b.launch_waves = kWavesPerWg;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, stream, b);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     if (ev0) SS_HIP_CHECK(hipEventRecord(ev0, stream), "hipEventRecord");
     hipLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
-                       dim3(64 * kWavesPerWg), 0, stream, b, b.block_table, b.tile_prefix, b.kv_len, b.q_indptr,
+                       dim3(64 * kWavesPerWg), 0, stream, b, b.tile_addr, b.tile_prefix, b.kv_len, b.q_indptr,
                        b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
     if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
@@ -506,13 +535,14 @@ int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, 
 
 }  // namespace
 
-size_t attn_workspace_bytes(int batch, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves)
+size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves)
 {
     const int G = num_q_heads / num_kv_heads;
     const size_t rows_pad = align_up((size_t)SS_OUT_WIDTH * G, 16);
     const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
     size_t n = 256;
     n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);
+    n += align_up(sizeof(int32_t) * (size_t)batch * max_blocks * num_kv_heads, 256);
     n += align_up(slots * rows_pad * 2 * sizeof(float), 256);
     n += align_up(slots * rows_pad * (size_t)head_dim * sizeof(float), 256);
     return n;

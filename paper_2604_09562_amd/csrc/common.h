@@ -50,13 +50,15 @@ struct AttnArgs {
     // workspace carve-up
     AttnPlan *plan;
     int32_t *tile_prefix;  // [batch+1] exclusive prefix of ceil(kv_len/16)
+    int32_t *tile_addr;    // [batch*max_blocks*kv_heads] flat tile list: physical block * kv_heads + kv head
     float *part_o;         // [slots][rows_pad][head_dim]
     float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
     int32_t rows_pad;      // query rows per (request, kv head), padded to 16
     int32_t launch_waves;  // upper bound of streaming wavefronts (sizes the partial slots)
 };
 
-size_t attn_workspace_bytes(int batch, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves);
+size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim,
+                            int launch_waves);
 bool attn_mfma_supported(const AttnArgs &a);
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 int32_t attn_generic_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
