@@ -46,28 +46,55 @@ constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
 {
-    __shared__ int sh[4];
+    __shared__ int sh[8];
     const int b = blockIdx.x / a.num_kv_heads, g = blockIdx.x % a.num_kv_heads;
     const int tid = threadIdx.x;
-    int part = 0;
-    for (int i = tid; i < b; i += 256) part += (a.kv_len[i] + kTile - 1) / kTile;
-    for (int off = 32; off; off >>= 1) part += __shfl_xor(part, off);
-    if ((tid & 63) == 0) sh[tid >> 6] = part;
+    int before = 0, rest = 0;   // tiles (per kv head) of the requests in front of b, and from b on
+    for (int i = tid; i < a.batch; i += 256) {
+        const int t = (a.kv_len[i] + kTile - 1) / kTile;
+        if (i < b) before += t; else rest += t;
+    }
+    for (int off = 32; off; off >>= 1) {
+        before += __shfl_xor(before, off);
+        rest += __shfl_xor(rest, off);
+    }
+    if ((tid & 63) == 0) {
+        sh[tid >> 6] = before;
+        sh[4 + (tid >> 6)] = rest;
+    }
     __syncthreads();
     const int pre = sh[0] + sh[1] + sh[2] + sh[3];
+    const long long total = (long long)(pre + sh[4] + sh[5] + sh[6] + sh[7]) * a.num_kv_heads;
+    long long nw = total / kMinTilesPerWave;
+    if (nw < 1) nw = 1;
+    if (nw > a.launch_waves) nw = a.launch_waves;
+
     const int n = (a.kv_len[b] + kTile - 1) / kTile;
+    const long long off = (long long)pre * a.num_kv_heads + (long long)g * n;   // this unit's place in the flat list
     const int32_t *bt = a.block_table + (long long)b * a.max_blocks;
-    int32_t *dst = a.tile_addr + (long long)pre * a.num_kv_heads + (long long)g * n;
+    int32_t *dst = a.tile_addr + off;
     for (int t = tid; t < n; t += 256) dst[t] = bt[t] * a.num_kv_heads + g;
+
+    // waves whose span [w*total/nw, (w+1)*total/nw) starts inside this unit get their descriptor here
+    const long long w_lo = (off * nw + total - 1) / total;             // first w with w*total/nw >= off
+    const long long w_hi = ((off + n) * nw + total - 1) / total;       // first w with w*total/nw >= off + n
+    for (long long w = w_lo + tid; w < w_hi && w < nw; w += 256) {
+        const long long x0 = w * total / nw, x1 = (w + 1) * total / nw;
+        int32_t *d = a.wave_desc + w * 8;
+        d[0] = b; d[1] = g; d[2] = (int)(x0 - off); d[3] = n;
+        d[4] = (int)x0; d[5] = (int)x1; d[6] = 0; d[7] = 0;
+    }
+    if (blockIdx.x == 0) {   // launched waves beyond the partition count get an empty span
+        for (long long w = nw + tid; w < a.launch_waves; w += 256) {
+            int32_t *d = a.wave_desc + w * 8;
+            d[4] = 0;
+            d[5] = 0;
+        }
+    }
     if (g == 0 && tid == 0) {
         a.tile_prefix[b] = pre;
         if (b == a.batch - 1) {
-            const int per_head = pre + n;
-            a.tile_prefix[a.batch] = per_head;
-            const long long total = (long long)per_head * a.num_kv_heads;
-            long long nw = total / kMinTilesPerWave;
-            if (nw < 1) nw = 1;
-            if (nw > a.launch_waves) nw = a.launch_waves;
+            a.tile_prefix[a.batch] = pre + n;
             a.plan->total_tiles = (int)total;
             a.plan->num_waves = (int)nw;
         }
@@ -148,7 +175,8 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 // OCC   wavefronts per SIMD the register budget is sized for
 template <int G, int NB, bool FP8, int NBUF, int OCC>
 __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
-    AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ tile_prefix,
+    AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
+    const int32_t *__restrict__ tile_prefix,
     const int32_t *__restrict__ kv_len, const int32_t *__restrict__ q_indptr, const float *__restrict__ k_scale,
     const float *__restrict__ v_scale)
 {
@@ -163,36 +191,19 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
     int32_t *ids = id_lds[wslot];
 
-    const int num_waves = a.plan->num_waves;
-    const long long total = a.plan->total_tiles;
-    if (wave >= num_waves) return;
-    const long long x0 = (long long)wave * total / num_waves;      // this wave's span of the flat tile list
-    const long long x1 = (long long)(wave + 1) * total / num_waves;
-    if (x0 >= x1) return;
-
-    // unit holding tile x0: largest b with Hkv * tile_prefix[b] <= x0
-    const long long per_head_x = x0 / a.num_kv_heads;
-    int b = -1;
-    for (int base = 0; base <= a.batch; base += 64) {
-        const int idx = base + lane;
-        const bool le = idx <= a.batch && (long long)tile_prefix[idx] <= per_head_x;
-        b += __popcll(__ballot(le));
-    }
-    if (b >= a.batch) b = a.batch - 1;  // x0 < total, so this only guards against bad plans
-    int nb_tiles;
-    int g, tile;
+    // where this wave's span starts: written by the plan kernel (waves past the partition count get x0 == x1)
+    int b, g, tile, nb_tiles;
+    long long x0, x1;
     {
-        const int pre = tile_prefix[b];
-        nb_tiles = tile_prefix[b + 1] - pre;
-        const long long rem = x0 - (long long)pre * a.num_kv_heads;
-        g = (int)(rem / nb_tiles);
-        tile = (int)(rem % nb_tiles);
+        const int32_t *d = wave_desc + (long long)wave * 8;
+        b = d[0]; g = d[1]; tile = d[2]; nb_tiles = d[3];
+        x0 = d[4]; x1 = d[5];
     }
+    if (x0 >= x1) return;
 
     // ---- state of the unit being computed ----
     int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
     int seg_left = 0;                 // of those, tiles that still belong to the current unit
-    bool fresh = true;                // the next tile starts a unit segment
     int L = 0, q0 = 0, q_len = 0, rows = 0;
     bf16x8 qreg[NB][4];               // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
     int lim[NB];                      // last visible cache position of this lane's row in block nb
@@ -200,11 +211,23 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     float4v acc[8][NB];
     const float sc2 = a.sm_scale * kLog2e;
 
-    auto begin_unit = [&]() {
-        L = kv_len[b];
-        q0 = q_indptr[b];
-        q_len = q_indptr[b + 1] - q0;
+    // kv_len / q_indptr / tile count of the unit after the current one, fetched a unit ahead
+    int meta_L = kv_len[b], meta_q0 = q_indptr[b], meta_q1 = q_indptr[b + 1], meta_nbt = nb_tiles;
+    auto begin_unit_issue = [&]() {
+        L = meta_L;
+        q0 = meta_q0;
+        q_len = meta_q1 - meta_q0;
+        nb_tiles = meta_nbt;
         rows = q_len * G;
+        {
+            const int nb_ = (g + 1 == a.num_kv_heads) ? b + 1 : b;   // request of the next unit
+            if (nb_ != b && nb_ < a.batch) {
+                meta_L = kv_len[nb_];
+                meta_q0 = q_indptr[nb_];
+                meta_q1 = q_indptr[nb_ + 1];
+                meta_nbt = tile_prefix[nb_ + 1] - tile_prefix[nb_];
+            }
+        }
         seg_left = nb_tiles - tile < span_left ? nb_tiles - tile : span_left;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -226,8 +249,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
 #pragma unroll
             for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
         }
-        // Have the queries arrive here, inside the rarely taken branch, so that the steady-state
-        // path never carries a pending load of them.
+    };
+    // Have the queries arrive here, inside the rarely taken branch, so that the steady-state path
+    // never carries a pending load of them.
+    auto begin_unit_wait = [&]() {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -267,12 +292,11 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
                 }
             }
         }
-        // next unit
+        // next unit (its metadata is already in meta_*)
         tile = 0;
         if (++g == a.num_kv_heads) {
             g = 0;
             ++b;
-            if (b < a.batch) nb_tiles = tile_prefix[b + 1] - tile_prefix[b];
         }
     };
 
@@ -378,27 +402,46 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb], acc[mb][nb], 0, 0, 0);
     };
 
-    // one step of the compute side: open a unit segment if needed, consume a tile, close the segment
+    // one step of the compute side: consume a tile; at the end of a unit segment write its partial
+    // and open the next segment (its query loads go out ahead of the next KV prefetch)
     auto step = [&](const TileRegs<FP8> &t) {
-        if (fresh) {
-            begin_unit();
-            fresh = false;
-        }
         compute(t, tile);
         ++tile;
         --span_left;
         if (--seg_left == 0) {
             end_unit();
-            fresh = true;
+            if (span_left > 0) {
+                begin_unit_issue();
+                begin_unit_wait();
+            }
         }
     };
 
     // ---- load side: a linear walk over the span's tile addresses, staged in LDS a window at a time ----
+    bool first_window = true;
     for (long long c0 = x0; c0 < x1; c0 += kIdWindow) {
         const int n = (int)(x1 - c0 < kIdWindow ? x1 - c0 : kIdWindow);
-        for (int i = lane; i < n; i += 64) ids[i] = tile_addr[c0 + i];
-        int p_load = 0;
-        int id_v = ids[0];   // address of the next tile to load, read from LDS one step ahead of its use
+        // the window's addresses: vector reads now, into LDS once they have arrived
+        int idtmp[kIdWindow / 64];
+#pragma unroll
+        for (int i = 0; i < kIdWindow / 64; ++i) idtmp[i] = (i * 64 + lane < n) ? tile_addr[c0 + i * 64 + lane] : 0;
+        // the first NBUF-1 tiles do not wait for that: their addresses come by scalar reads
+        int first_addr[NBUF - 1];
+#pragma unroll
+        for (int j = 0; j < NBUF - 1; ++j) first_addr[j] = tile_addr[c0 + (j < n ? j : n - 1)];
+        if (first_window) begin_unit_issue();   // queries of the first unit go out before any KV tile
+
+        TileRegs<FP8> buf[NBUF];
+#pragma unroll
+        for (int j = 0; j < NBUF - 1; ++j)
+            if (j < n) load_tile<FP8>(buf[j], a, k_scale, v_scale, first_addr[j], lane, vzero);
+        if (first_window) begin_unit_wait();
+        first_window = false;
+#pragma unroll
+        for (int i = 0; i < kIdWindow / 64; ++i) ids[i * 64 + lane] = idtmp[i];
+
+        int p_load = NBUF - 1;   // next tile of the window to load
+        int id_v = ids[p_load < n ? p_load : n - 1];   // its address, read from LDS one step ahead of its use
         auto issue = [&](TileRegs<FP8> &t) {
             const int addr = __builtin_amdgcn_readfirstlane(id_v);
             ++p_load;
@@ -410,23 +453,14 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         // The steady-state loop issues its prefetch unconditionally, so the wait before each
         // compute only covers the tile it needs and NBUF-1 tiles stay in flight; the last few
         // tiles of a window (and short windows) run through a conditional epilogue.
-        TileRegs<FP8> buf[NBUF];
         int p = 0;
-        if (n >= 2 * NBUF - 1) {
+        for (; p + 2 * NBUF - 2 < n; p += NBUF) {
 #pragma unroll
-            for (int j = 0; j < NBUF - 1; ++j) issue(buf[j]);
-            for (; p + 2 * NBUF - 2 < n; p += NBUF) {
-#pragma unroll
-                for (int j = 0; j < NBUF; ++j) {
-                    issue(buf[(j + NBUF - 1) % NBUF]);
-                    __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
-                    step(buf[j]);
-                }
+            for (int j = 0; j < NBUF; ++j) {
+                issue(buf[(j + NBUF - 1) % NBUF]);
+                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
+                step(buf[j]);
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NBUF - 1; ++j)
-                if (j < n) issue(buf[j]);
         }
         // here buf[j] holds tile p + j for j < NBUF-1 (as far as such tiles exist)
 #pragma unroll
@@ -492,10 +526,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 template <int G, int NB, bool FP8>
 int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
-    // Up to two row blocks fit the register file twice per SIMD; beyond that one wave per SIMD
-    // with a deeper ring keeps the same number of bytes in flight per compute unit.
-    constexpr int OCC = NB <= 2 ? 2 : 1;
-    constexpr int NBUF = NB <= 2 ? 2 : (FP8 ? 4 : 3);
+    // One wave per SIMD with three tiles in flight: two waves on a SIMD do not share the memory
+    // pipeline fairly under saturation (the older one wins), which turns into a long tail.
+    constexpr int OCC = 1;
+    constexpr int NBUF = NB <= 3 ? 4 : 3;
     AttnArgs b = a;
     b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
     b.launch_waves -= b.launch_waves % kWavesPerWg;
@@ -504,7 +538,7 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     if (ev0) SS_HIP_CHECK(hipEventRecord(ev0, stream), "hipEventRecord");
     hipLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
-                       dim3(64 * kWavesPerWg), 0, stream, b, b.tile_addr, b.tile_prefix, b.kv_len, b.q_indptr,
+                       dim3(64 * kWavesPerWg), 0, stream, b, b.tile_addr, b.wave_desc, b.tile_prefix, b.kv_len, b.q_indptr,
                        b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
     if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
@@ -542,6 +576,7 @@ size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_
     const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
     size_t n = 256;
     n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);
+    n += align_up(sizeof(int32_t) * 8 * (size_t)launch_waves, 256);
     n += align_up(sizeof(int32_t) * (size_t)batch * max_blocks * num_kv_heads, 256);
     n += align_up(slots * rows_pad * 2 * sizeof(float), 256);
     n += align_up(slots * rows_pad * (size_t)head_dim * sizeof(float), 256);

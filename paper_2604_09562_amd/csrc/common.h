@@ -51,6 +51,7 @@ struct AttnArgs {
     AttnPlan *plan;
     int32_t *tile_prefix;  // [batch+1] exclusive prefix of ceil(kv_len/16)
     int32_t *tile_addr;    // [batch*max_blocks*kv_heads] flat tile list: physical block * kv_heads + kv head
+    int32_t *wave_desc;    // [launch_waves][8]: where each wave's span starts (request, kv head, tile, ...)
     float *part_o;         // [slots][rows_pad][head_dim]
     float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
     int32_t rows_pad;      // query rows per (request, kv head), padded to 16
