@@ -24,6 +24,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the streaming kernel from the committed counter summary, if there is one.
+
+    The figure comes from two rocprofv3 --pmc runs of this script (FETCH_SIZE, WRITE_SIZE) scaled by the
+    calibration copy; the summary file carries it on a line `traffic_bytes_per_launch: N`."""
+    path = os.path.join(ROOT, "profiles", f"attn_stream_kernel_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, att, acc, budget_requests: int):
     """The oracle as it stands, timed on this host on the first `budget_requests` requests."""
     import oracle
@@ -54,7 +70,11 @@ def main() -> int:
     ap.add_argument("--config", default="llama3_8b_b64")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=4, help="distinct copies of cache and logits cycled through")
-    ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-requests", type=int, default=-1,
+                    help="requests in the CPU-oracle sample (0 = skip, -1 = the whole batch)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="after timing, launch a plain device copy of this size three times: the known-size "
+                         "kernel that scales FETCH_SIZE / WRITE_SIZE in a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
     ap.add_argument("--attn-waves", type=int, default=0, help="KV partitions of the attention kernel (0 = automatic)")
     args = ap.parse_args()
@@ -146,7 +166,7 @@ def main() -> int:
                    "kv_tokens": int(att["kv_len"].astype(np.int64).sum()), "vocab": cfg.vocab,
                    "max_q_len": max_q_len, "rotated_copies": nrot, "seed": args.seed},
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg.name),
                      "algorithmic_bytes": kv_bytes, "kernel_ms_avg": kern_avg_ms,
                      "kernel_ms_min": float(np.min(kern_ms)) if len(kern_ms) else None, "launches": int(len(kern_ms))},
         "kv_read_gbps": achieved, "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
@@ -169,8 +189,15 @@ def main() -> int:
         if not err <= tol + 1e-2 * float(np.max(np.abs(ref[r0:r1]))):
             print(f"bench.py: parity spot check failed (max abs err {err})", file=sys.stderr)
             return 4
-    if args.cpu_requests > 0:
-        result["cpu_baseline"] = cpu_baseline(cfg, att, acc, args.cpu_requests)
+    if args.cpu_requests != 0:
+        n_cpu = att["batch"] if args.cpu_requests < 0 else args.cpu_requests
+        result["cpu_baseline"] = cpu_baseline(cfg, att, acc, n_cpu)
+    if args.calibrate_copy > 0:
+        src = torch.empty(args.calibrate_copy << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(result))
     return 0
 
