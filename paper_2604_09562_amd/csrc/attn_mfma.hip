@@ -22,6 +22,8 @@
 // needed (only a 16-bit pack per operand register).
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "common.h"
 
 namespace ss {
@@ -173,7 +175,10 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 // NB    16-row blocks of query rows the kernel is compiled for (covers max_q_len * G rows)
 // NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
 // OCC   wavefronts per SIMD the register budget is sized for
-template <int G, int NB, bool FP8, int NBUF, int OCC>
+// QLDS  keep the query operands in LDS (in operand order, one 1 KB line per row block and k-step)
+//       instead of registers: for many row blocks the registers are needed for the accumulators
+// SPLIT row blocks from SPLIT on are skipped for units with fewer rows (== NB: nothing is skipped)
+template <int G, int NB, bool FP8, int NBUF, int OCC, bool QLDS, int SPLIT>
 __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
     const int32_t *__restrict__ tile_prefix,
@@ -183,6 +188,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     // The metadata arrays come in as separate no-alias arguments so that their wave-uniform reads
     // become scalar loads (own counter, no ordering against the vector KV loads).
     __shared__ int32_t id_lds[kWavesPerWg][kIdWindow];
+    __shared__ uint4 q_lds[QLDS ? kWavesPerWg * NB * 4 * 64 : 1];
     const int lane = threadIdx.x & 63;
     const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = blockIdx.x * kWavesPerWg + wslot;
@@ -190,6 +196,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     int vzero;
     asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
     int32_t *ids = id_lds[wslot];
+    uint4 *qs = q_lds + (QLDS ? wslot * NB * 4 * 64 : 0) + (QLDS ? lane : 0);
 
     // where this wave's span starts: written by the plan kernel (waves past the partition count get x0 == x1)
     int b, g, tile, nb_tiles;
@@ -204,8 +211,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     // ---- state of the unit being computed ----
     int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
     int seg_left = 0;                 // of those, tiles that still belong to the current unit
-    int L = 0, q0 = 0, q_len = 0, rows = 0;
-    bf16x8 qreg[NB][4];               // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
+    int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has
+    bf16x8 qreg[QLDS ? 1 : NB][4];    // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
     int lim[NB];                      // last visible cache position of this lane's row in block nb
     float m_run[NB], l_run[NB];
     float4v acc[8][NB];
@@ -219,6 +226,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         q_len = meta_q1 - meta_q0;
         nb_tiles = meta_nbt;
         rows = q_len * G;
+        nbu = (rows + 15) >> 4;
         {
             const int nb_ = (g + 1 == a.num_kv_heads) ? b + 1 : b;   // request of the next unit
             if (nb_ != b && nb_ < a.batch) {
@@ -242,7 +250,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
                 const int d0 = FP8 ? ((ks >> 1) * 64 + jq * 16 + (ks & 1) * 8) : (ks * 32 + jq * 8);
                 uint4 w = make_uint4(0, 0, 0, 0);
                 if (ok) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
-                qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
+                if constexpr (QLDS)
+                    qs[(nb * 4 + ks) * 64] = w;
+                else
+                    qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
             }
             m_run[nb] = kNoMax;
             l_run[nb] = 0.f;
@@ -253,10 +264,12 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     // Have the queries arrive here, inside the rarely taken branch, so that the steady-state path
     // never carries a pending load of them.
     auto begin_unit_wait = [&]() {
+        if constexpr (!QLDS) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+                for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+        }
     };
 
     auto end_unit = [&]() {
@@ -264,7 +277,6 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         // states a read needs before anything below touches them.
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-        const int nbu = (rows + 15) >> 4;
         const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
         float *po = a.part_o + slot * a.rows_pad * D;
         float *pml = a.part_ml + slot * a.rows_pad * 2;
@@ -300,11 +312,89 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         }
     };
 
-    // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond this
-    // unit's rows hold zero queries; they are computed anyway (cheaper than branching) and never
-    // stored.  The body is straight-line code apart from the rare rescale: masks are selects that
-    // are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
-    // its result: the wait states the hardware needs there are only inserted inside a block.)
+    // Row blocks [LO, HI) against one tile: S^T = K Q^T, softmax, O^T += V^T P^T.  Straight-line
+    // code apart from the rare rescale: masks are selects that are all-pass on ordinary tiles.
+    // (No branch may sit between an MFMA and the first read of its result: the wait states the
+    // hardware needs there are only inserted inside a block.)
+    auto rows_range = [&](auto lo_c, auto hi_c, const TileRegs<FP8> &t, const short4v (&vop)[8], const bf16x8 (&kop)[4],
+                          int tok0) {
+        constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
+        float4v s[HI - LO];
+#pragma unroll
+        for (int nb = LO; nb < HI; ++nb) s[nb - LO] = float4v{0.f, 0.f, 0.f, 0.f};
+        if constexpr (QLDS) {
+            // operands come from LDS a few MFMAs ahead of their use, so that its latency is covered
+            constexpr int NOPS = 4 * (HI - LO), AHEAD = NOPS < 6 ? NOPS : 6;
+            uint4 qb[AHEAD];
+#pragma unroll
+            for (int i = 0; i < AHEAD; ++i) qb[i] = qs[((LO + i % (HI - LO)) * 4 + i / (HI - LO)) * 64];
+#pragma unroll
+            for (int i = 0; i < NOPS; ++i) {
+                const int ks = i / (HI - LO), nb = LO + i % (HI - LO);
+                const bf16x8 qop = __builtin_bit_cast(bf16x8, qb[i % AHEAD]);
+                if (i + AHEAD < NOPS) {
+                    const int i2 = i + AHEAD;
+                    qb[i % AHEAD] = qs[((LO + i2 % (HI - LO)) * 4 + i2 / (HI - LO)) * 64];
+                }
+                s[nb - LO] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qop, s[nb - LO], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int nb = LO; nb < HI; ++nb)
+                    s[nb - LO] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb - LO], 0, 0, 0);
+        }
+
+        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
+        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
+        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
+        const float kscale = sc2 * t.ks;
+        float sv[HI - LO][4];
+        bool trig = false;
+#pragma unroll
+        for (int nb = LO; nb < HI; ++nb) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                sv[nb - LO][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb - LO][e] * kscale;
+            const float lane_mx = fmaxf(fmaxf(sv[nb - LO][0], sv[nb - LO][1]), fmaxf(sv[nb - LO][2], sv[nb - LO][3]));
+            trig |= lane_mx > m_run[nb] + kSlack;
+        }
+        if (__any(trig)) {
+#pragma unroll
+            for (int nb = LO; nb < HI; ++nb) {
+                float mx = fmaxf(fmaxf(sv[nb - LO][0], sv[nb - LO][1]), fmaxf(sv[nb - LO][2], sv[nb - LO][3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[nb], mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+                l_run[nb] *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
+                m_run[nb] = m_new;
+            }
+        }
+        short4v pop[HI - LO];
+#pragma unroll
+        for (int nb = LO; nb < HI; ++nb) {
+            float p[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb - LO][e] - m_run[nb]);
+            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+            uint2 pk;
+            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            pop[nb - LO] = __builtin_bit_cast(short4v, pk);
+        }
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+            for (int nb = LO; nb < HI; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb - LO], acc[mb][nb], 0, 0, 0);
+    };
+
+    // One tile: operand registers of K and V, then the row blocks.
     auto compute = [&](const TileRegs<FP8> &t, int ti) {
         const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
         // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
@@ -345,61 +435,13 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
         }
-        float4v s[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
-
-        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
-        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
-        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
-        const float kscale = sc2 * t.ks;
-        float sv[NB][4];
-        bool trig = false;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
-            const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-            trig |= lane_mx > m_run[nb] + kSlack;
+        // Row blocks [0, SPLIT) are always computed (blocks beyond the unit's rows hold zero queries:
+        // cheaper than branching, never stored); the rest only for units that have that many rows.
+        rows_range(std::integral_constant<int, 0>{}, std::integral_constant<int, SPLIT>{}, t, vop, kop, tok0);
+        if constexpr (SPLIT < NB) {
+            if (nbu > SPLIT)
+                rows_range(std::integral_constant<int, SPLIT>{}, std::integral_constant<int, NB>{}, t, vop, kop, tok0);
         }
-        if (__any(trig)) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[nb], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-                l_run[nb] *= alpha;
-#pragma unroll
-                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
-                m_run[nb] = m_new;
-            }
-        }
-        short4v pop[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
-            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
-            uint2 pk;
-            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-            pop[nb] = __builtin_bit_cast(short4v, pk);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb], acc[mb][nb], 0, 0, 0);
     };
 
     // one step of the compute side: consume a tile; at the end of a unit segment write its partial
@@ -529,19 +571,21 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     // One wave per SIMD with three tiles in flight: two waves on a SIMD do not share the memory
     // pipeline fairly under saturation (the older one wins), which turns into a long tail.
     constexpr int OCC = 1;
-    constexpr int NBUF = NB <= 3 ? 4 : 3;
+    constexpr bool QLDS = NB >= 4;
+    constexpr int SPLIT = NB == 5 ? 3 : NB == 4 ? 2 : NB;
+    constexpr int NBUF = NB <= 3 ? 4 : (NB == 5 && !FP8) ? 2 : 3;
     AttnArgs b = a;
     b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
     b.launch_waves -= b.launch_waves % kWavesPerWg;
     if (b.launch_waves < kWavesPerWg) b.launch_waves = kWavesPerWg;
     hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
-    if (ev0) SS_HIP_CHECK(hipEventRecord(ev0, stream), "hipEventRecord");
-    hipLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
-                       dim3(64 * kWavesPerWg), 0, stream, b, b.tile_addr, b.wave_desc, b.tile_prefix, b.kv_len, b.q_indptr,
-                       b.k_scale, b.v_scale);
+    // When a profile is being taken the two events are attached to the dispatch itself, so that
+    // their difference is the kernel's own duration on this stream (what a kernel trace shows).
+    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC, QLDS, SPLIT>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
+                          dim3(64 * kWavesPerWg), 0, stream, ev0, ev1, 0, b, b.tile_addr, b.wave_desc, b.tile_prefix,
+                          b.kv_len, b.q_indptr, b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
-    if (ev1) SS_HIP_CHECK(hipEventRecord(ev1, stream), "hipEventRecord");
     hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads * (a.rows_pad / kMergeRows)), dim3(256),
                        0, stream, b);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_merge_kernel");
