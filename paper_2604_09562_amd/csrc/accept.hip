@@ -65,48 +65,79 @@ __host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
 // Coalesced order: lane t owns entries base + it*(256*vec) + t*vec + j (vec = 8 for bf16, 4 for f32).
 // Sequential order (the inverse-CDF search): lane t owns base + t*N .. + N-1.
 // Out-of-vocabulary positions read as -inf.  index_of() gives the vocabulary id of slot s.
-template <int N, bool SEQ>
-__device__ __forceinline__ int index_of(int base, int tid, int s, int dtype)
+// DT is the logit dtype (SS_BF16 or SS_F32): the kernels are compiled once per dtype.
+template <int DT, int N, bool SEQ>
+__device__ __forceinline__ int index_of(int base, int tid, int s)
 {
     if (SEQ) return base + tid * N + s;
-    const int vec = dtype == SS_BF16 ? 8 : 4;
+    constexpr int vec = DT == SS_BF16 ? 8 : 4;
     return base + (s / vec) * (kThreads * vec) + tid * vec + (s % vec);
 }
 
-template <int N, bool SEQ>
-__device__ __forceinline__ void load_slots(const void *row, int vocab, int base, int tid, int dtype, float (&x)[N])
+template <int DT, int N, bool SEQ>
+__device__ __forceinline__ void load_slots(const void *row, int vocab, int base, int tid, float (&x)[N])
 {
-    if (dtype == SS_BF16) {
+    constexpr int vec = DT == SS_BF16 ? 8 : 4;
+    if (base + N * kThreads <= vocab) {   // whole block inside the vocabulary (uniform): plain 16-byte loads
+        uint4 w[N / vec];
 #pragma unroll
-        for (int it = 0; it < N / 8; ++it) {
-            const int i0 = index_of<N, SEQ>(base, tid, it * 8, dtype);
-            if (i0 + 8 <= vocab) {
-                const uint4 w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + i0);
-                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        for (int it = 0; it < N / vec; ++it) {
+            const int i0 = index_of<DT, N, SEQ>(base, tid, it * vec);
+            if constexpr (DT == SS_BF16)
+                w[it] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + i0);
+            else
+                w[it] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(row) + i0);
+        }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+        for (int it = 0; it < N / vec; ++it) {
+            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (DT == SS_BF16) {
                     x[it * 8 + 2 * j] = __uint_as_float(ww[j] << 16);
                     x[it * 8 + 2 * j + 1] = __uint_as_float(ww[j] & 0xffff0000u);
+                } else {
+                    x[it * 4 + j] = __uint_as_float(ww[j]);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    x[it * 8 + j] = (i0 + j < vocab)
-                                        ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(row)[i0 + j] << 16)
-                                        : -INFINITY;
             }
         }
-    } else {
+        return;
+    }
+    // The block that holds the end of the vocabulary.  Every lane still issues 16-byte loads (from a
+    // clamped, in-bounds address, so that they pipeline); lanes whose vector lies past the end drop
+    // the data, and the one vector that straddles the end is read element by element.
+    const int last_full = vocab >= vec ? (vocab - vec) / vec * vec : -1;
 #pragma unroll
-        for (int it = 0; it < N / 4; ++it) {
-            const int i0 = index_of<N, SEQ>(base, tid, it * 4, dtype);
-            if (i0 + 4 <= vocab) {
-                const float4 w = *reinterpret_cast<const float4 *>(static_cast<const float *>(row) + i0);
-                x[it * 4] = w.x; x[it * 4 + 1] = w.y; x[it * 4 + 2] = w.z; x[it * 4 + 3] = w.w;
+    for (int it = 0; it < N / vec; ++it) {
+        const int i0 = index_of<DT, N, SEQ>(base, tid, it * vec);
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (last_full >= 0) {
+            const int ic = i0 < last_full ? i0 : last_full;
+            if constexpr (DT == SS_BF16)
+                w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + ic);
+            else
+                w = *reinterpret_cast<const uint4 *>(static_cast<const float *>(row) + ic);
+        }
+        const bool whole = i0 + vec <= vocab;
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (DT == SS_BF16) {
+                x[it * 8 + 2 * j] = whole ? __uint_as_float(ww[j] << 16) : -INFINITY;
+                x[it * 8 + 2 * j + 1] = whole ? __uint_as_float(ww[j] & 0xffff0000u) : -INFINITY;
             } else {
+                x[it * 4 + j] = whole ? __uint_as_float(ww[j]) : -INFINITY;
+            }
+        }
+        if (!whole && i0 < vocab) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    x[it * 4 + j] = (i0 + j < vocab) ? static_cast<const float *>(row)[i0 + j] : -INFINITY;
+            for (int j = 0; j < vec; ++j) {
+                if (i0 + j < vocab) {
+                    if constexpr (DT == SS_BF16)
+                        x[it * vec + j] = __uint_as_float((uint32_t) static_cast<const uint16_t *>(row)[i0 + j] << 16);
+                    else
+                        x[it * vec + j] = static_cast<const float *>(row)[i0 + j];
+                }
             }
         }
     }
@@ -155,7 +186,7 @@ struct ExpTable {
     }
     __device__ __forceinline__ double operator()(double x) const
     {
-        if (!(x > -745.0)) return 0.0;  // underflow (also -inf)
+        x = fmax(x, -746.0);   // exp underflows to 0 from there on (also covers -inf)
         const double kd = rint(x * 92.33248261689366);  // 64 / ln 2
         double r = fma(kd, -0x1.62e42fee00000p-7, x);    // ln2/64: high part with 21 trailing zero bits
         r = fma(kd, -0x1.a39ef35793c76p-39, r);          //         low part
@@ -168,6 +199,7 @@ struct ExpTable {
 // ---- pass 1 ---------------------------------------------------------------------------------
 // grid: batch * kMaxRows * nchunks; workgroup (b, j, chunk) handles chunk `chunk` of request b's row j
 // (j <= k: target row j; k < j <= 2k: draft row j-k-1; larger j: nothing to do).
+template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ float sh[4];
@@ -179,9 +211,9 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
     const bool is_draft = j > k;
     const int r = is_draft ? t0 - b + (j - k - 1) : t0 + j;
     const int64_t ry = is_draft ? (int64_t)a.total_rows + r : r;
-    const void *row = row_ptr(is_draft ? a.draft : a.target, r, a.row_stride, a.logit_dtype);
+    const void *row = row_ptr(is_draft ? a.draft : a.target, r, a.row_stride, DT);
     float x[kPerThread];
-    load_slots<kPerThread, false>(row, a.vocab, chunk * kChunk, tid, a.logit_dtype, x);
+    load_slots<DT, kPerThread, false>(row, a.vocab, chunk * kChunk, tid, x);
 
     float m = x[0];
 #pragma unroll
@@ -193,7 +225,7 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
         int best = 0x7fffffff;
 #pragma unroll
         for (int s = 0; s < kPerThread; ++s) {
-            const int id = index_of<kPerThread, false>(chunk * kChunk, tid, s, a.logit_dtype);
+            const int id = index_of<DT, kPerThread, false>(chunk * kChunk, tid, s);
             if (x[s] == cm && id < best) best = id;
         }
         for (int off = 32; off; off >>= 1) best = min(best, __shfl_xor(best, off));
@@ -308,6 +340,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
 }
 
 // ---- pass 2a: fp64 normalisers per block ----------------------------------------------------
+template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
@@ -317,11 +350,9 @@ __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Wor
     const RowPick pk = w.pick[b];
     const double inv_t = 1.0 / (double)pk.temperature;
     float xp[kSubPer], xq[kSubPer];
-    load_slots<kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
-                               a.logit_dtype, xp);
+    load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xp);
     if (pk.q_row >= 0)
-        load_slots<kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
-                                   a.logit_dtype, xq);
+        load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
     double z = 0.0;
 #pragma unroll
     for (int s = 0; s < kSubPer; ++s) z += ex(((double)xp[s] - (double)pk.m_p) * inv_t);
@@ -355,6 +386,7 @@ __device__ __forceinline__ double mass(const ExpTable &ex, float lp, float lq, c
 }
 
 // ---- pass 2b: residual mass per block -------------------------------------------------------
+template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_mass_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
@@ -368,10 +400,8 @@ __global__ __launch_bounds__(kThreads) void accept_mass_kernel(AcceptArgs a, Wor
     }
     ex.init();
     float xp[kSubPer], xq[kSubPer];
-    load_slots<kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
-                               a.logit_dtype, xp);
-    load_slots<kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, sub * kSub, tid,
-                               a.logit_dtype, xq);
+    load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xp);
+    load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
     const double zq = block_total(w.zq + (int64_t)b * w.nsub, w.nsub, sh);
     const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
     double s = 0.0;
@@ -382,6 +412,7 @@ __global__ __launch_bounds__(kThreads) void accept_mass_kernel(AcceptArgs a, Wor
 }
 
 // ---- pass 2c: inverse-CDF search ------------------------------------------------------------
+template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double wave_tot[4];
@@ -436,11 +467,11 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
         // p_n == q_n exactly: no residual mass; fall back to the lowest-index argmax of the target row
         float best = -INFINITY;
         for (int v = tid; v < a.vocab; v += kThreads)
-            best = fmaxf(best, load_logit(a.target, pk.p_row, a.row_stride, a.logit_dtype, v));
+            best = fmaxf(best, load_logit(a.target, pk.p_row, a.row_stride, DT, v));
         best = block_max(best, sh_f);
         int arg = 0x7fffffff;
         for (int v = tid; v < a.vocab; v += kThreads)
-            if (load_logit(a.target, pk.p_row, a.row_stride, a.logit_dtype, v) == best) { arg = v; break; }
+            if (load_logit(a.target, pk.p_row, a.row_stride, DT, v) == best) { arg = v; break; }
         for (int off = 32; off; off >>= 1) arg = min(arg, __shfl_xor(arg, off));
         if (lane == 0) sh_first[wave] = arg;
         __syncthreads();
@@ -462,11 +493,9 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     const double zq = pk.q_row >= 0 ? block_total(w.zq + (int64_t)b * w.nsub, w.nsub, wave_tot) : 1.0;
     const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
     float xp[kSubPer], xq[kSubPer];
-    load_slots<kSubPer, true>(row_ptr(a.target, pk.p_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kSub, tid,
-                              a.logit_dtype, xp);
+    load_slots<DT, kSubPer, true>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, cstar * kSub, tid, xp);
     if (pk.q_row >= 0)
-        load_slots<kSubPer, true>(row_ptr(a.draft, pk.q_row, a.row_stride, a.logit_dtype), a.vocab, cstar * kSub, tid,
-                                  a.logit_dtype, xq);
+        load_slots<DT, kSubPer, true>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, cstar * kSub, tid, xq);
     else {
 #pragma unroll
         for (int i = 0; i < kSubPer; ++i) xq[i] = 0.f;
@@ -532,6 +561,23 @@ size_t accept_workspace_bytes(int batch, int total_rows, int vocab)
     return n + 256;
 }
 
+template <int DT>
+static int32_t accept_launch_dt(const AcceptArgs &a, const Workspace &w, unsigned g1, unsigned g2, hipStream_t stream)
+{
+    hipLaunchKernelGGL(accept_rowstats_kernel<DT>, dim3(g1), dim3(kThreads), 0, stream, a, w);
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_decide_kernel");
+    if (a.greedy) return SS_OK;
+    hipLaunchKernelGGL(accept_norm_kernel<DT>, dim3(g2), dim3(kThreads), 0, stream, a, w);
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_norm_kernel");
+    hipLaunchKernelGGL(accept_mass_kernel<DT>, dim3(g2), dim3(kThreads), 0, stream, a, w);
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_mass_kernel");
+    hipLaunchKernelGGL(accept_pick_kernel<DT>, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_pick_kernel");
+    return SS_OK;
+}
+
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
 {
     const Workspace w = carve(a.workspace, a.batch, a.total_rows, a.vocab);
@@ -539,18 +585,8 @@ int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
     const unsigned long long g2 = (unsigned long long)a.batch * w.nsub;
     if (g1 > 0x7fffffffull || g2 > 0x7fffffffull)
         return fail(SS_ERR_UNSUPPORTED, "batch * vocab too large for one launch");
-    hipLaunchKernelGGL(accept_rowstats_kernel, dim3((unsigned)g1), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_decide_kernel");
-    if (a.greedy) return SS_OK;
-    hipLaunchKernelGGL(accept_norm_kernel, dim3((unsigned)g2), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_norm_kernel");
-    hipLaunchKernelGGL(accept_mass_kernel, dim3((unsigned)g2), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_mass_kernel");
-    hipLaunchKernelGGL(accept_pick_kernel, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_pick_kernel");
-    return SS_OK;
+    if (a.logit_dtype == SS_BF16) return accept_launch_dt<SS_BF16>(a, w, (unsigned)g1, (unsigned)g2, stream);
+    return accept_launch_dt<SS_F32>(a, w, (unsigned)g1, (unsigned)g2, stream);
 }
 
 }  // namespace ss
