@@ -151,7 +151,7 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.tile_prefix = reinterpret_cast<int32_t *>(w);
     w += align_up(sizeof(int32_t) * ((size_t)batch->batch + 1), 256);
     a.wave_desc = reinterpret_cast<int32_t *>(w);
-    w += align_up(sizeof(int32_t) * 8 * (size_t)launch_waves, 256);
+    w += align_up(sizeof(int32_t) * kDescInts * (size_t)launch_waves, 256);
     a.tile_addr = reinterpret_cast<int32_t *>(w);
     w += align_up(sizeof(int32_t) * (size_t)batch->batch * batch->max_blocks_per_seq * kv->num_kv_heads, 256);
     const size_t slots = (size_t)launch_waves + (size_t)batch->batch * kv->num_kv_heads;

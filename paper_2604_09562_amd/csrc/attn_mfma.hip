@@ -80,15 +80,37 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     // waves whose span [w*total/nw, (w+1)*total/nw) starts inside this unit get their descriptor here
     const long long w_lo = (off * nw + total - 1) / total;             // first w with w*total/nw >= off
     const long long w_hi = ((off + n) * nw + total - 1) / total;       // first w with w*total/nw >= off + n
+    // Descriptor: {request, kv head, first tile, tiles of the unit, span begin, span end, kv_len,
+    // first query row, end query row, addresses of the span's first kDescAddrs tiles}: everything
+    // the wave's first loads depend on, so that they go out after a single read.
     for (long long w = w_lo + tid; w < w_hi && w < nw; w += 256) {
         const long long x0 = w * total / nw, x1 = (w + 1) * total / nw;
-        int32_t *d = a.wave_desc + w * 8;
+        int32_t *d = a.wave_desc + w * kDescInts;
         d[0] = b; d[1] = g; d[2] = (int)(x0 - off); d[3] = n;
-        d[4] = (int)x0; d[5] = (int)x1; d[6] = 0; d[7] = 0;
+        d[4] = (int)x0; d[5] = (int)x1;
+        d[6] = a.kv_len[b]; d[7] = a.q_indptr[b]; d[8] = a.q_indptr[b + 1];
+        // walk forward from (b, g, tile) over unit boundaries; past the last unit repeat the last tile
+        int bb = b, gg = g, tt = (int)(x0 - off), nn = n, last = 0;
+        const int32_t *tb = bt;
+        for (int j = 0; j < kDescAddrs; ++j) {
+            while (bb < a.batch && tt >= nn) {
+                tt -= nn;
+                if (++gg == a.num_kv_heads) {
+                    gg = 0;
+                    if (++bb < a.batch) {
+                        nn = (a.kv_len[bb] + kTile - 1) / kTile;
+                        tb = a.block_table + (long long)bb * a.max_blocks;
+                    }
+                }
+            }
+            if (bb < a.batch) last = tb[tt] * a.num_kv_heads + gg;
+            d[9 + j] = last;
+            ++tt;
+        }
     }
     if (blockIdx.x == 0) {   // launched waves beyond the partition count get an empty span
         for (long long w = nw + tid; w < a.launch_waves; w += 256) {
-            int32_t *d = a.wave_desc + w * 8;
+            int32_t *d = a.wave_desc + w * kDescInts;
             d[4] = 0;
             d[5] = 0;
         }
@@ -201,11 +223,17 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     // where this wave's span starts: written by the plan kernel (waves past the partition count get x0 == x1)
     int b, g, tile, nb_tiles;
     long long x0, x1;
+    int meta_L, meta_q0, meta_q1, meta_nbt;   // kv_len / q_indptr / tile count of the next unit to open
+    int desc_addr[kDescAddrs];
     {
-        const int32_t *d = wave_desc + (long long)wave * 8;
+        const int32_t *d = wave_desc + (long long)wave * kDescInts;
         b = d[0]; g = d[1]; tile = d[2]; nb_tiles = d[3];
         x0 = d[4]; x1 = d[5];
+        meta_L = d[6]; meta_q0 = d[7]; meta_q1 = d[8]; meta_nbt = nb_tiles;
+#pragma unroll
+        for (int j = 0; j < kDescAddrs; ++j) desc_addr[j] = d[9 + j];
     }
+    static_assert(NBUF - 1 <= kDescAddrs, "descriptor carries too few tile addresses");
     if (x0 >= x1) return;
 
     // ---- state of the unit being computed ----
@@ -218,8 +246,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     float4v acc[8][NB];
     const float sc2 = a.sm_scale * kLog2e;
 
-    // kv_len / q_indptr / tile count of the unit after the current one, fetched a unit ahead
-    int meta_L = kv_len[b], meta_q0 = q_indptr[b], meta_q1 = q_indptr[b + 1], meta_nbt = nb_tiles;
+    // (the metadata of the unit after the current one is fetched a unit ahead)
     auto begin_unit_issue = [&]() {
         L = meta_L;
         q0 = meta_q0;
@@ -470,7 +497,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         // the first NBUF-1 tiles do not wait for that: their addresses come by scalar reads
         int first_addr[NBUF - 1];
 #pragma unroll
-        for (int j = 0; j < NBUF - 1; ++j) first_addr[j] = tile_addr[c0 + (j < n ? j : n - 1)];
+        for (int j = 0; j < NBUF - 1; ++j)
+            first_addr[j] = first_window ? desc_addr[j] : tile_addr[c0 + (j < n ? j : n - 1)];
         if (first_window) begin_unit_issue();   // queries of the first unit go out before any KV tile
 
         TileRegs<FP8> buf[NBUF];
@@ -620,7 +648,7 @@ size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_
     const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
     size_t n = 256;
     n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);
-    n += align_up(sizeof(int32_t) * 8 * (size_t)launch_waves, 256);
+    n += align_up(sizeof(int32_t) * kDescInts * (size_t)launch_waves, 256);
     n += align_up(sizeof(int32_t) * (size_t)batch * max_blocks * num_kv_heads, 256);
     n += align_up(slots * rows_pad * 2 * sizeof(float), 256);
     n += align_up(slots * rows_pad * (size_t)head_dim * sizeof(float), 256);

@@ -25,6 +25,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int kTile = SS_BLOCK_SIZE;     // tokens per KV tile = tokens per cache block
 constexpr int kWavesPerWg = 4;
 constexpr int kMinTilesPerWave = 8;      // below this a KV partition is not worth its partial write
+constexpr int kDescInts = 16;            // ints per wave descriptor
+constexpr int kDescAddrs = 4;            // tile addresses a descriptor carries for the span's first tiles
 
 // Written by the plan kernel, read by the streaming and merge kernels.
 struct AttnPlan {
@@ -51,7 +53,7 @@ struct AttnArgs {
     AttnPlan *plan;
     int32_t *tile_prefix;  // [batch+1] exclusive prefix of ceil(kv_len/16)
     int32_t *tile_addr;    // [batch*max_blocks*kv_heads] flat tile list: physical block * kv_heads + kv head
-    int32_t *wave_desc;    // [launch_waves][8]: where each wave's span starts (request, kv head, tile, ...)
+    int32_t *wave_desc;    // [launch_waves][kDescInts]: where each wave's span starts and what its first loads need
     float *part_o;         // [slots][rows_pad][head_dim]
     float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
     int32_t rows_pad;      // query rows per (request, kv head), padded to 16
