@@ -40,6 +40,9 @@ def _load():
         lib.oracle_spec_accept.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_decode.restype = None
+        lib.oracle_encode.restype = None
+        lib.oracle_kv_append.restype = ctypes.c_int
+        lib.oracle_kv_commit.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -112,3 +115,32 @@ def spec_accept(inp: Dict[str, object], *, greedy: Optional[bool] = None, tie_ep
         raise ValueError(f"oracle_spec_accept rejected its arguments (code {rc})")
     return dict(accepted_len=accepted, out_tokens=toks, ratio=ratio[:Rd], near_tie=near[:Rd],
                 y_lo=ylo, y_hi=yhi, resid_sum=rsum)
+
+
+def encode(x: np.ndarray, dtype: str) -> np.ndarray:
+    """float32 -> bfloat16 bits (uint16) or e4m3fn bytes (uint8, |x| <= 448), nearest, ties to even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16 if dtype == "bf16" else np.uint8)
+    _load().oracle_encode(_p(x), ctypes.c_int64(x.size), ctypes.c_int(_DT[dtype]), _p(out))
+    return out
+
+
+def kv_append(inp: Dict[str, object]) -> None:
+    """Write the new tokens' K/V of a batch dict from ``synth.make_append_inputs`` into its cache, in place."""
+    rc = _load().oracle_kv_append(
+        ctypes.c_int(inp["batch"]), ctypes.c_int(inp["num_kv_heads"]), ctypes.c_int(inp["head_dim"]),
+        ctypes.c_int(inp["block_size"]), ctypes.c_int(inp["max_blocks_per_seq"]), ctypes.c_int(_DT[inp["kv_dtype"]]),
+        _p(inp["k_cache"]), _p(inp["v_cache"]), _p(inp["k_scale"]), _p(inp["v_scale"]), _p(inp["block_table"]),
+        _p(inp["kv_len"]), _p(inp["q_indptr"]), ctypes.c_int(_DT[inp["new_dtype"]]), _p(inp["k_new"]), _p(inp["v_new"]))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_append rejected its arguments (code {rc})")
+
+
+def kv_commit(q_indptr: np.ndarray, accepted_len: np.ndarray, kv_len: np.ndarray) -> np.ndarray:
+    """Valid cache length of every request after acceptance (a new array)."""
+    out = np.ascontiguousarray(kv_len, dtype=np.int32).copy()
+    rc = _load().oracle_kv_commit(ctypes.c_int(len(out)), _p(np.ascontiguousarray(q_indptr, dtype=np.int32)),
+                                  _p(np.ascontiguousarray(accepted_len, dtype=np.int32)), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_commit rejected its arguments (code {rc})")
+    return out

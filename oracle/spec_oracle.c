@@ -21,7 +21,7 @@
  *
  * Pin status: every function in this file is pinned by tests/test_oracle_*.py
  * (library attention routine, brute force, closed forms, exhaustive
- * enumeration of the sampling identity).  Accepted-length statistics on the
+ * enumeration of the sampling identity, library storage casts).  Accepted-length statistics on the
  * five workloads are "parity unpinned" by the paper (it prints none).
  */
 #include <math.h>
@@ -419,6 +419,146 @@ int oracle_spec_accept(int B, int V, int64_t row_stride, int logit_dtype, const 
         free(p);
     }
     return fail ? -5 : 0;
+}
+
+/* ---- KV append and commit (the steps around verification) --------------------
+ *
+ * Section 3.4, Eq. 7: the decode worker's KV is the prefill KV with every new
+ * token's key/value appended.  Before a verification step the k_b+1 new tokens
+ * of request b (last accepted token + drafts) are written to the last q_len of
+ * the kv_len[b] cache positions: row i of the request goes to position
+ * pos = kv_len - q_len + i, i.e. physical block block_table[b][pos/bs], slot
+ * pos%bs, for every KV head.  New keys/values arrive as [row][kv head][d] in
+ * float32 or bfloat16 and are stored in the cache's format:
+ *   float32 cache   the value itself;
+ *   bfloat16 cache  the nearest bfloat16, ties to the even mantissa;
+ *   e4m3 cache      byte = nearest e4m3fn to clamp(x / scale, +-448), ties to
+ *                   even, with x / scale taken in float32 (one IEEE division);
+ *                   scale is one float32 per (block, kv head).  A block whose
+ *                   slot 0 is written by this call gets a new scale = amax / 448
+ *                   (float32 division; 1.0 if amax == 0), amax over this call's
+ *                   values for that block and head, keys and values separately;
+ *                   a block that already held older tokens keeps its scale.
+ *
+ * After acceptance, request b keeps its n_b accepted drafts: the valid length
+ * becomes kv_len - k_b + n_b (the token drawn by the acceptance step is the
+ * first query token of the next step and is appended then).  Rejected slots
+ * simply fall beyond the valid length.
+ *
+ * Pins: tests/test_oracle_kv.py (round trip through an independently built
+ * cache, library bfloat16/e4m3 casts, a hand-worked scale example, a token-list
+ * simulation of commit).
+ */
+static uint16_t encode_bf16(float f)
+{
+    uint32_t w;
+    memcpy(&w, &f, 4);
+    if (isnan(f))
+        return (uint16_t)((w >> 16) | 0x40);
+    uint16_t lo = (uint16_t)(w >> 16);   /* towards zero */
+    uint16_t hi = (uint16_t)(lo + 1);    /* next one away from zero */
+    double x = fabs((double)f), a = fabs(decode_bf16(lo));
+    double b = ((hi & 0x7F80) == 0x7F80) ? ldexp(1.0, 128) : fabs(decode_bf16(hi)); /* infinity stands for 2^128 */
+    double da = x - a, db = b - x;
+    if (da < db) return lo;
+    if (db < da) return hi;
+    return (lo & 1) ? hi : lo;
+}
+
+static uint8_t encode_e4m3fn(float q) /* q finite, |q| <= 448 */
+{
+    int neg = signbit(q) ? 1 : 0, best = -1;
+    double x = fabs((double)q), bd = 0.0;
+    for (int c = 0; c < 0x7F; ++c) { /* all finite magnitudes */
+        double d = fabs(decode_e4m3fn((uint8_t)c) - x);
+        if (best < 0 || d < bd || (d == bd && (c & 1) == 0 && (best & 1) == 1)) {
+            best = c;
+            bd = d;
+        }
+    }
+    return (uint8_t)(best | (neg << 7));
+}
+
+static float new_value(const void *src, int64_t idx, int dtype)
+{
+    if (dtype == OR_F32) return ((const float *)src)[idx];
+    return (float)decode_bf16(((const uint16_t *)src)[idx]);
+}
+
+int oracle_kv_append(int B, int Hkv, int D, int bs, int max_blocks, int kv_dtype, void *k_cache, void *v_cache,
+                     float *k_scale, float *v_scale, const int32_t *block_table, const int32_t *kv_len,
+                     const int32_t *q_indptr, int new_dtype, const void *k_new, const void *v_new)
+{
+    if (B < 0 || Hkv <= 0 || D <= 0 || bs <= 0 || (new_dtype != OR_F32 && new_dtype != OR_BF16)) return -1;
+    if (kv_dtype == OR_FP8_E4M3 && (!k_scale || !v_scale)) return -2;
+    for (int b = 0; b < B; ++b) {
+        int q_len = q_indptr[b + 1] - q_indptr[b], L = kv_len[b];
+        if (q_len < 1 || L < q_len || (L + bs - 1) / bs > max_blocks) return -3;
+    }
+    for (int side = 0; side < 2; ++side) {
+        void *cache = side ? v_cache : k_cache;
+        float *scale = side ? v_scale : k_scale;
+        const void *src = side ? v_new : k_new;
+        for (int b = 0; b < B; ++b) {
+            int r0 = q_indptr[b], q_len = q_indptr[b + 1] - r0, P = kv_len[b] - q_len;
+            for (int h = 0; h < Hkv; ++h) {
+                if (kv_dtype == OR_FP8_E4M3) { /* scales of the blocks this call starts */
+                    for (int blk = P / bs; blk <= (kv_len[b] - 1) / bs; ++blk) {
+                        if (blk * bs < P) continue; /* holds older tokens: scale stays */
+                        float amax = 0.f;
+                        for (int i = 0; i < q_len; ++i)
+                            if ((P + i) / bs == blk)
+                                for (int d = 0; d < D; ++d) {
+                                    float a = fabsf(new_value(src, ((int64_t)(r0 + i) * Hkv + h) * D + d, new_dtype));
+                                    if (a > amax) amax = a;
+                                }
+                        int phys = block_table[(int64_t)b * max_blocks + blk];
+                        scale[(int64_t)phys * Hkv + h] = amax > 0.f ? amax / 448.0f : 1.0f;
+                    }
+                }
+                for (int i = 0; i < q_len; ++i) {
+                    int pos = P + i, phys = block_table[(int64_t)b * max_blocks + pos / bs];
+                    int64_t dst = (((int64_t)phys * Hkv + h) * bs + pos % bs) * D;
+                    for (int d = 0; d < D; ++d) {
+                        float x = new_value(src, ((int64_t)(r0 + i) * Hkv + h) * D + d, new_dtype);
+                        if (kv_dtype == OR_F32) {
+                            ((float *)cache)[dst + d] = x;
+                        } else if (kv_dtype == OR_BF16) {
+                            ((uint16_t *)cache)[dst + d] = encode_bf16(x);
+                        } else {
+                            float q = x / scale[(int64_t)phys * Hkv + h];
+                            if (q > 448.0f) q = 448.0f;
+                            if (q < -448.0f) q = -448.0f;
+                            ((uint8_t *)cache)[dst + d] = isnan(q) ? 0x7F : encode_e4m3fn(q);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_kv_commit(int B, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len)
+{
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (accepted_len[b] < 0 || accepted_len[b] > k) return -1;
+    }
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        kv_len[b] = kv_len[b] - k + accepted_len[b];
+    }
+    return 0;
+}
+
+/* for tests: the two storage encoders on arrays */
+void oracle_encode(const float *src, int64_t n, int dtype, void *dst)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        if (dtype == OR_BF16) ((uint16_t *)dst)[i] = encode_bf16(src[i]);
+        else ((uint8_t *)dst)[i] = isnan(src[i]) ? 0x7F : encode_e4m3fn(src[i]);
+    }
 }
 
 int oracle_num_threads(void)

@@ -228,6 +228,32 @@ def make_attention_inputs(cfg: VerifyConfig, seed: int = 0, *,
     )
 
 
+def make_append_inputs(cfg: VerifyConfig, seed: int = 0, **kw) -> Dict[str, object]:
+    """A batch for kv_append: the attention batch with the new tokens' cache slots poisoned, plus
+    the new keys/values ``k_new``/``v_new`` [total_rows][kv heads][head_dim] (N(0,1), float32 for a
+    float32 cache, bfloat16 bits otherwise) that the append has to write there.  For e4m3 caches the
+    scales of the blocks this step starts are poisoned too (the append must set them)."""
+    inp = make_attention_inputs(cfg, seed, **kw)
+    B, Hkv, D, R = inp["batch"], inp["num_kv_heads"], inp["head_dim"], inp["total_rows"]
+    rng = _rng(cfg, seed, 9)
+    new_dtype = "f32" if cfg.kv_dtype == "f32" else "bf16"
+    inp["new_dtype"] = new_dtype
+    inp["k_new"] = store(rng.standard_normal((R, Hkv, D), dtype=np.float32), new_dtype)
+    inp["v_new"] = store(rng.standard_normal((R, Hkv, D), dtype=np.float32), new_dtype)
+    poison = {"f32": np.float32(np.nan), "bf16": np.uint16(0x7FC0), "fp8": np.uint8(0x7F)}[cfg.kv_dtype]
+    for b in range(B):
+        q_len = int(inp["q_indptr"][b + 1] - inp["q_indptr"][b])
+        L = int(inp["kv_len"][b])
+        for pos in range(L - q_len, L):
+            phys = inp["block_table"][b, pos // BLOCK_SIZE]
+            inp["k_cache"][phys, :, pos % BLOCK_SIZE, :] = poison
+            inp["v_cache"][phys, :, pos % BLOCK_SIZE, :] = poison
+            if cfg.kv_dtype == "fp8" and pos % BLOCK_SIZE == 0:
+                inp["k_scale"][phys, :] = np.nan
+                inp["v_scale"][phys, :] = np.nan
+    return inp
+
+
 def _sample_rows_inverse_cdf(logits: np.ndarray, T: np.ndarray, u: np.ndarray) -> np.ndarray:
     """Draw one token per row from softmax(logits/T) (draft-model sampling: workload, not verification)."""
     out = np.empty(len(logits), dtype=np.int32)

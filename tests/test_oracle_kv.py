@@ -1,0 +1,191 @@
+"""Pins of the oracle's KV append / commit (the steps around verification; Section 3.4, Eq. 7).
+
+The append is pinned against things the oracle did not produce: a paged cache that the input
+generator built with its own code (round trip), PyTorch's bfloat16 and float8_e4m3fn casts
+(library routines), a scale example worked by hand, and a token-list simulation of commit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_09562_amd import synth
+
+TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
+
+
+def small(cfg, **kw):
+    return cfg.scaled(**kw)
+
+
+def new_values_from_cache(inp):
+    """The new tokens' K/V as they sit in a generator-built cache (storage format, [R][Hkv][D])."""
+    B, Hkv, D, R = inp["batch"], inp["num_kv_heads"], inp["head_dim"], inp["total_rows"]
+    k = np.empty((R, Hkv, D), dtype=inp["k_cache"].dtype)
+    v = np.empty_like(k)
+    for b in range(B):
+        r0, r1 = inp["q_indptr"][b], inp["q_indptr"][b + 1]
+        L = int(inp["kv_len"][b])
+        for i in range(r1 - r0):
+            pos = L - (r1 - r0) + i
+            phys = inp["block_table"][b, pos // 16]
+            k[r0 + i] = inp["k_cache"][phys, :, pos % 16, :]
+            v[r0 + i] = inp["v_cache"][phys, :, pos % 16, :]
+    return k, v
+
+
+@pytest.mark.parametrize("cfg", [small(TINY), small(LLAMA8B, batch=6, ctx=("uniform", 17, 200)),
+                                 small(RAGGED, batch=12, ctx=("uniform", 9, 120))], ids=["f32", "bf16", "ragged"])
+def test_round_trip_through_generator_built_cache(oracle, cfg):
+    # Take a cache the generator filled, lift the new tokens' K/V out, wipe their slots, append them
+    # again: every byte of the cache must come back.  Pins position, block table, slot, head and
+    # element order against the generator's independent layout code.
+    ref = synth.make_attention_inputs(cfg, seed=3)
+    k_new, v_new = new_values_from_cache(ref)
+    inp = synth.make_append_inputs(cfg, seed=3)
+    assert not np.array_equal(inp["k_cache"].view(np.uint8), ref["k_cache"].view(np.uint8))
+    inp["k_new"], inp["v_new"] = k_new, v_new
+    oracle.kv_append(inp)
+    assert np.array_equal(inp["k_cache"].view(np.uint8), ref["k_cache"].view(np.uint8))
+    assert np.array_equal(inp["v_cache"].view(np.uint8), ref["v_cache"].view(np.uint8))
+
+
+def test_append_then_attend_equals_attention_on_generator_cache(oracle):
+    cfg = small(LLAMA8B, batch=4, ctx=("uniform", 20, 90))
+    ref = synth.make_attention_inputs(cfg, seed=1)
+    inp = synth.make_append_inputs(cfg, seed=1)
+    inp["k_new"], inp["v_new"] = new_values_from_cache(ref)
+    oracle.kv_append(inp)
+    o1, l1 = oracle.verify_attn(ref)
+    o2, l2 = oracle.verify_attn(inp)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_f32_values_into_bf16_cache_match_library_cast(oracle):
+    # float32 keys/values into a bfloat16 cache: the stored bits are torch's round-to-nearest-even cast
+    cfg = small(LLAMA8B, batch=3, ctx=("uniform", 17, 80))
+    inp = synth.make_append_inputs(cfg, seed=2)
+    rng = np.random.default_rng(5)
+    shape = inp["k_new"].shape
+    kf = rng.standard_normal(shape).astype(np.float32) * np.float32(3.0)
+    vf = rng.standard_normal(shape).astype(np.float32)
+    # plant exact ties and extremes
+    kf.flat[:6] = np.array([1.00390625, 1.01171875, -1.00390625, 3.3895314e38, 1e-40, -0.0], dtype=np.float32)
+    inp["k_new"], inp["v_new"], inp["new_dtype"] = kf, vf, "f32"
+    oracle.kv_append(inp)
+    got_k, got_v = new_values_from_cache(inp)
+    want_k = torch.from_numpy(kf).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    want_v = torch.from_numpy(vf).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got_k, want_k) and np.array_equal(got_v, want_v)
+
+
+def test_encoders_match_library_casts(oracle):
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * np.float32(100.0),
+                        rng.uniform(-448, 448, 20000).astype(np.float32),
+                        rng.standard_normal(5000).astype(np.float32) * np.float32(0.01),
+                        np.array([0.0, -0.0, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 0.0009765625,
+                                  17.0, 18.0, 19.0, 21.0, 0.0078125 * 1.5], dtype=np.float32)])
+    xc = np.clip(x, -448, 448).astype(np.float32)
+    want8 = torch.from_numpy(xc).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got8 = oracle.encode(xc, "fp8")
+    assert np.array_equal(got8, want8)
+    want16 = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.encode(x, "bf16"), want16)
+    # and the encoder inverts the decoder on every finite code
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = oracle.decode(codes, "fp8").astype(np.float32)
+    assert np.array_equal(oracle.encode(vals, "fp8"), codes)
+
+
+def test_fp8_scale_rule_by_hand(oracle):
+    # One request, one KV head, head_dim 2, kv_len 18, three new tokens at positions 15, 16, 17:
+    # position 15 lands in block 0, which holds older tokens (scale stays 0.5); positions 16, 17
+    # start block 1, whose scale becomes amax/448 of what lands there.
+    bt = np.array([[1, 0]], dtype=np.int32)   # logical block 0 -> physical 1, logical 1 -> physical 0
+    inp = dict(batch=1, num_kv_heads=1, head_dim=2, block_size=16, max_blocks_per_seq=2, kv_dtype="fp8",
+               k_cache=np.zeros((2, 1, 16, 2), dtype=np.uint8), v_cache=np.zeros((2, 1, 16, 2), dtype=np.uint8),
+               k_scale=np.array([[np.nan], [0.5]], dtype=np.float32), v_scale=np.array([[np.nan], [0.25]], dtype=np.float32),
+               block_table=bt, kv_len=np.array([18], dtype=np.int32), q_indptr=np.array([0, 3], dtype=np.int32),
+               new_dtype="f32",
+               k_new=np.array([[[1.0, -300.0]], [[7.0, -3.5]], [[0.875, 14.0]]], dtype=np.float32),
+               v_new=np.array([[[0.5, 0.0]], [[-2.0, 1.0]], [[0.0, 0.0]]], dtype=np.float32))
+    oracle.kv_append(inp)
+    # keys: block 0 (physical 1) keeps 0.5: 1.0/0.5 = 2 -> 0x40; -300/0.5 = -600 -> clamps to -448 = 0xFE
+    assert inp["k_scale"][1, 0] == np.float32(0.5)
+    assert inp["k_cache"][1, 0, 15].tolist() == [0x40, 0xFE]
+    # block 1 (physical 0): amax = 14 -> scale 14/448 = 1/32; 7*32 = 224 -> 0x76, -3.5*32 = -112 -> 0xEE,
+    # 0.875*32 = 28 -> 0x5E, 14*32 = 448 -> 0x7E
+    assert inp["k_scale"][0, 0] == np.float32(14.0) / np.float32(448.0)
+    assert inp["k_cache"][0, 0, 0].tolist() == [0x76, 0xEE]
+    assert inp["k_cache"][0, 0, 1].tolist() == [0x5E, 0x7E]
+    # values: 0.5/0.25 = 2 -> 0x40, 0 -> 0x00; block 1: amax 2 -> scale 2/448; -2 -> -448 = 0xFE, 1 -> 224 = 0x76
+    assert inp["v_cache"][1, 0, 15].tolist() == [0x40, 0x00]
+    assert inp["v_scale"][0, 0] == np.float32(2.0) / np.float32(448.0)
+    assert inp["v_cache"][0, 0, 0].tolist() == [0xFE, 0x76]
+    assert inp["v_cache"][0, 0, 1].tolist() == [0x00, 0x00]
+    # untouched slots stay untouched
+    assert not inp["k_cache"][1, 0, :15].any() and not inp["k_cache"][0, 0, 2:].any()
+
+
+def test_fp8_block_boundary_and_positive_clamp_by_hand(oracle):
+    # kv_len 18, two new tokens at positions 16 and 17: the first new position IS slot 0 of block 1,
+    # so block 1 gets a new scale and block 0 is not touched at all.  A second request writes 300 into
+    # an old block with scale 0.5: 600 clamps to +448.
+    bt = np.array([[0, 1], [2, -1]], dtype=np.int32)
+    inp = dict(batch=2, num_kv_heads=1, head_dim=1, block_size=16, max_blocks_per_seq=2, kv_dtype="fp8",
+               k_cache=np.zeros((3, 1, 16, 1), dtype=np.uint8), v_cache=np.zeros((3, 1, 16, 1), dtype=np.uint8),
+               k_scale=np.array([[0.125], [np.nan], [0.5]], dtype=np.float32),
+               v_scale=np.array([[0.125], [np.nan], [0.5]], dtype=np.float32),
+               block_table=bt, kv_len=np.array([18, 5], dtype=np.int32), q_indptr=np.array([0, 2, 3], dtype=np.int32),
+               new_dtype="f32", k_new=np.array([[[4.0]], [[-1.0]], [[300.0]]], dtype=np.float32),
+               v_new=np.array([[[0.0]], [[0.0]], [[-1.0]]], dtype=np.float32))
+    oracle.kv_append(inp)
+    assert inp["k_scale"][0, 0] == np.float32(0.125) and not inp["k_cache"][0].any()
+    assert inp["k_scale"][1, 0] == np.float32(4.0) / np.float32(448.0)
+    assert inp["k_cache"][1, 0, :2, 0].tolist() == [0x7E, 0xEE]        # 448, -112
+    assert inp["v_scale"][1, 0] == np.float32(1.0)                      # all-zero block: scale 1
+    assert inp["k_cache"][2, 0, 4, 0] == 0x7E and inp["k_scale"][2, 0] == np.float32(0.5)   # +600 -> +448
+    assert inp["v_cache"][2, 0, 4, 0] == 0xC0                          # -1/0.5 = -2
+
+
+def test_fp8_append_dequantises_close_to_the_values(oracle):
+    cfg = small(FP8_70B, batch=5, ctx=("uniform", 17, 150))
+    inp = synth.make_append_inputs(cfg, seed=4)
+    oracle.kv_append(inp)
+    assert not np.isnan(inp["k_scale"][inp["block_table"][inp["block_table"] >= 0]]).any()
+    k_bytes, v_bytes = new_values_from_cache(inp)
+    want = synth.decode_storage(inp["k_new"], "bf16")
+    for b in range(inp["batch"]):
+        r0, r1 = inp["q_indptr"][b], inp["q_indptr"][b + 1]
+        L = int(inp["kv_len"][b])
+        for i in range(r1 - r0):
+            pos = L - (r1 - r0) + i
+            phys = inp["block_table"][b, pos // 16]
+            deq = oracle.decode(k_bytes[r0 + i], "fp8") * inp["k_scale"][phys][:, None].astype(np.float64)
+            sc = inp["k_scale"][phys][:, None].astype(np.float64)
+            fresh = (pos // 16) * 16 >= L - (r1 - r0)
+            # e4m3 keeps 4 significant bits: relative error <= 2^-4, absolute <= half a subnormal step
+            err = np.abs(deq - want[r0 + i])
+            bound = np.maximum(np.abs(want[r0 + i]) * 2.0 ** -4, sc * 2.0 ** -10)
+            ok = err <= bound + 1e-12
+            if not fresh:   # older scale may clip large values
+                ok |= np.abs(want[r0 + i]) >= 448 * sc
+            assert ok.all()
+
+
+def test_commit_against_token_list_simulation(oracle):
+    rng = np.random.default_rng(0)
+    B = 50
+    k = rng.integers(0, 9, B)
+    ctx = rng.integers(9, 500, B)
+    n = np.array([rng.integers(0, kk + 1) for kk in k])
+    q_indptr = np.zeros(B + 1, dtype=np.int32)
+    q_indptr[1:] = np.cumsum(k + 1)
+    got = oracle.kv_commit(q_indptr, n.astype(np.int32), ctx.astype(np.int32))
+    for b in range(B):
+        cache = list(range(ctx[b] - (k[b] + 1))) + ["t"] + [f"d{i}" for i in range(k[b])]   # old tokens, last accepted, drafts
+        assert len(cache) == ctx[b]
+        kept = cache[:ctx[b] - (k[b] + 1)] + ["t"] + [f"d{i}" for i in range(n[b])]
+        assert got[b] == len(kept)
+    with pytest.raises(ValueError):
+        oracle.kv_commit(np.array([0, 3], dtype=np.int32), np.array([3], dtype=np.int32), np.array([10], dtype=np.int32))
