@@ -189,6 +189,27 @@ def main() -> int:
         if not err <= tol + 1e-2 * float(np.max(np.abs(ref[r0:r1]))):
             print(f"bench.py: parity spot check failed (max abs err {err})", file=sys.stderr)
             return 4
+    # the steps around the verify step (not part of the timed step): append the new tokens' K/V, commit lengths
+    rng = np.random.default_rng(args.seed)
+    shape = (q_tokens, cfg.num_kv_heads, cfg.head_dim)
+    new_dtype = "f32" if cfg.kv_dtype == "f32" else "bf16"
+    d_app = dict(d_att[0], new_dtype=new_dtype,
+                 k_new=binding._to_dev(synth.store(rng.standard_normal(shape, dtype=np.float32), new_dtype), dev),
+                 v_new=binding._to_dev(synth.store(rng.standard_normal(shape, dtype=np.float32), new_dtype), dev))
+    lens = d_att[0]["kv_len"].clone()
+    t_app, t_com = [], []
+    for i in range(8):
+        ev[0].record()
+        binding.ss_kv_append(d_app)
+        ev[1].record()
+        binding.ss_kv_commit(d_att[0]["q_indptr"], n_acc, lens)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_app.append(ev[0].elapsed_time(ev[1]))
+        t_com.append(ev[1].elapsed_time(ev[2]))
+        lens.copy_(d_att[0]["kv_len"])
+    result["t_kv_append_ms"] = float(np.median(t_app))
+    result["t_kv_commit_ms"] = float(np.median(t_com))
     if args.cpu_requests != 0:
         n_cpu = att["batch"] if args.cpu_requests < 0 else args.cpu_requests
         result["cpu_baseline"] = cpu_baseline(cfg, att, acc, n_cpu)

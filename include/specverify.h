@@ -167,6 +167,38 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
                        void *stream);
 
 /*
+ * KV append, the step before verification (paper Section 3.4, Eq. 7: the decode KV is the prefill KV
+ * with the new tokens' keys/values appended; Section 2.4: paged layout).  Request b's
+ * q_len = q_indptr[b+1]-q_indptr[b] new tokens are written to the last q_len of its kv_len[b] cache
+ * positions (kv_len already counts them): row i goes to position kv_len[b]-q_len+i, i.e. block
+ * block_table[b][pos/16], slot pos%16, for every KV head.
+ *   kv            the cache to write.  Its k, v (and for SS_FP8_E4M3 k_scale, v_scale) buffers are
+ *                 WRITTEN through although the struct declares them const for the read-only calls.
+ *   batch         block_table, kv_len, q_indptr as for ss_spec_verify_attn (max_q_len is ignored).
+ *   k_new, v_new  device, [total_rows][num_kv_heads][head_dim], dense, new_dtype = SS_F32 or SS_BF16.
+ * Stored as: SS_F32 cache the value; SS_BF16 cache nearest bfloat16, ties to even; SS_FP8_E4M3 cache
+ * byte = nearest e4m3fn (ties to even) of clamp(x / scale, +-448) with x / scale one float32
+ * division.  A block whose slot 0 is written by this call gets scale = amax / 448 (1.0 if amax is 0)
+ * over this call's values for that block and KV head, keys and values separately; a block that already
+ * holds older tokens keeps its scale.  NaN inputs give unspecified NaN payloads.
+ * The caller owns all buffers; nothing is allocated; the kernel is enqueued on `stream`.
+ * Errors: SS_ERR_INVALID_ARG (NULL pointers, bad dtypes or sizes), SS_ERR_DEVICE (launch failure).
+ * Device-side contents (block ids in range, kv_len >= q_len, q_len <= 9) are the caller's contract.
+ */
+int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k_new, const void *v_new,
+                     int32_t new_dtype, int32_t total_rows, void *stream);
+
+/*
+ * Commit after acceptance (same passage): request b keeps its accepted_len[b] accepted drafts, so its
+ * valid cache length becomes kv_len[b] - k_b + accepted_len[b] with k_b = q_indptr[b+1]-q_indptr[b]-1;
+ * the rejected slots fall past the end (no data moves), and the token the acceptance step drew is
+ * appended by the next step.  All arrays are device arrays; kv_len [batch] is updated in place.
+ * Errors: SS_ERR_INVALID_ARG (NULL pointers, negative batch), SS_ERR_DEVICE.
+ */
+int32_t ss_kv_commit(int32_t batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len,
+                     void *stream);
+
+/*
  * Options (process-wide, not thread-safe; meant for tests and measurement).
  *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
  *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic

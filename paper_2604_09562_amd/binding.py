@@ -21,8 +21,8 @@ SS_OUT_WIDTH = 9
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_set_option", "ss_profile_begin",
-           "ss_profile_collect")
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_kv_append", "ss_kv_commit", "ss_set_option",
+           "ss_profile_begin", "ss_profile_collect")
 
 
 class SpecVerifyError(RuntimeError):
@@ -70,6 +70,11 @@ def lib() -> ctypes.CDLL:
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.ss_kv_append.restype = ctypes.c_int32
+        L.ss_kv_append.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        L.ss_kv_commit.restype = ctypes.c_int32
+        L.ss_kv_commit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.ss_set_option.restype = ctypes.c_int32
         L.ss_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
         L.ss_profile_begin.restype = ctypes.c_int32
@@ -131,6 +136,14 @@ def attention_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, ob
     return d
 
 
+def append_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, object]:
+    """Copy one kv_append batch (attention batch + new keys/values) to the GPU, bytes unchanged."""
+    d = attention_to_device(inp, device)
+    for name in ("k_new", "v_new"):
+        d[name] = _to_dev(inp[name], device)
+    return d
+
+
 def accept_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, object]:
     d = dict(inp)
     for name in ("q_indptr", "target_logits", "draft_logits", "draft_tokens", "u_accept", "u_sample", "temperature"):
@@ -173,6 +186,18 @@ def alloc_attention_outputs(d: Dict[str, object], device="cuda:0", max_q_len: in
     lse = torch.empty(shape[:2], dtype=torch.float32, device=device)
     ws = torch.empty(max(ss_spec_verify_attn_workspace(d, max_q_len), 256), dtype=torch.uint8, device=device)
     return out, lse, ws
+
+
+def ss_kv_append(d: Dict[str, object]) -> None:
+    """Enqueue the append of `k_new`/`v_new` into the device batch's paged cache (written in place)."""
+    kv, bt = _descriptors(d, 0)
+    _check(lib().ss_kv_append(ctypes.byref(kv), ctypes.byref(bt), _ptr(d["k_new"]), _ptr(d["v_new"]),
+                              _DT[d["new_dtype"]], d["total_rows"], _stream()))
+
+
+def ss_kv_commit(q_indptr: torch.Tensor, accepted_len: torch.Tensor, kv_len: torch.Tensor) -> None:
+    """Enqueue kv_len[b] <- kv_len[b] - k_b + accepted_len[b] on device int32 tensors (kv_len in place)."""
+    _check(lib().ss_kv_commit(int(kv_len.numel()), _ptr(q_indptr), _ptr(accepted_len), _ptr(kv_len), _stream()))
 
 
 def ss_spec_accept_workspace(batch: int, total_rows: int, vocab: int) -> int:

@@ -222,6 +222,46 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     return accept_launch(a, static_cast<hipStream_t>(stream));
 }
 
+int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k_new, const void *v_new,
+                     int32_t new_dtype, int32_t total_rows, void *stream)
+{
+    if (!kv || !batch) return fail(SS_ERR_INVALID_ARG, "kv and batch descriptors must not be NULL");
+    if (kv->block_size != SS_BLOCK_SIZE)
+        return fail(SS_ERR_INVALID_ARG, "block_size must be %d, got %d", SS_BLOCK_SIZE, kv->block_size);
+    if (kv->head_dim != 64 && kv->head_dim != 128)
+        return fail(SS_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", kv->head_dim);
+    if (kv->num_kv_heads <= 0 || kv->num_blocks < 0) return fail(SS_ERR_INVALID_ARG, "bad num_kv_heads or num_blocks");
+    if (kv->dtype < SS_F32 || kv->dtype > SS_FP8_E4M3) return fail(SS_ERR_INVALID_ARG, "unknown KV dtype %d", kv->dtype);
+    if (new_dtype != SS_F32 && new_dtype != SS_BF16) return fail(SS_ERR_INVALID_ARG, "new_dtype must be SS_F32 or SS_BF16");
+    if (batch->batch < 0 || total_rows < batch->batch || (int64_t)total_rows > (int64_t)batch->batch * SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "total_rows (%d) must lie in [batch, %d*batch] for batch %d", total_rows,
+                    SS_OUT_WIDTH, batch->batch);
+    if (batch->batch == 0) return SS_OK;
+    if (batch->max_blocks_per_seq <= 0) return fail(SS_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
+    if ((int64_t)batch->batch * SS_OUT_WIDTH * kv->num_kv_heads > 0x7fffffffll)
+        return fail(SS_ERR_UNSUPPORTED, "batch * kv heads too large for one launch");
+    if (!kv->k || !kv->v || !batch->block_table || !batch->kv_len || !batch->q_indptr || !k_new || !v_new)
+        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if ((kv->dtype == SS_FP8_E4M3) != (kv->k_scale != nullptr) || (kv->k_scale != nullptr) != (kv->v_scale != nullptr))
+        return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
+    KvAppendArgs a{};
+    a.k = const_cast<void *>(kv->k); a.v = const_cast<void *>(kv->v);
+    a.k_scale = const_cast<float *>(kv->k_scale); a.v_scale = const_cast<float *>(kv->v_scale);
+    a.num_kv_heads = kv->num_kv_heads; a.head_dim = kv->head_dim; a.kv_dtype = kv->dtype;
+    a.batch = batch->batch; a.max_blocks = batch->max_blocks_per_seq;
+    a.block_table = batch->block_table; a.kv_len = batch->kv_len; a.q_indptr = batch->q_indptr;
+    a.k_new = k_new; a.v_new = v_new; a.new_dtype = new_dtype;
+    return kv_append_launch(a, static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_kv_commit(int32_t batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len, void *stream)
+{
+    if (batch < 0) return fail(SS_ERR_INVALID_ARG, "negative batch");
+    if (batch == 0) return SS_OK;
+    if (!q_indptr || !accepted_len || !kv_len) return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    return kv_commit_launch(batch, q_indptr, accepted_len, kv_len, static_cast<hipStream_t>(stream));
+}
+
 int32_t ss_profile_begin(int32_t max_calls)
 {
     if (max_calls < 0 || max_calls > 100000) return fail(SS_ERR_INVALID_ARG, "max_calls out of range");

@@ -85,4 +85,18 @@ struct AcceptArgs {
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream);
 
+// ---- KV append / commit ----------------------------------------------------------------------
+struct KvAppendArgs {
+    void *k, *v;
+    float *k_scale, *v_scale;
+    int32_t num_kv_heads, head_dim, kv_dtype;
+    int32_t batch, max_blocks;
+    const int32_t *block_table, *kv_len, *q_indptr;
+    const void *k_new, *v_new;
+    int32_t new_dtype;
+};
+int32_t kv_append_launch(const KvAppendArgs &a, hipStream_t stream);
+int32_t kv_commit_launch(int batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len,
+                         hipStream_t stream);
+
 }  // namespace ss
