@@ -199,6 +199,31 @@ int32_t ss_kv_commit(int32_t batch, const int32_t *q_indptr, const int32_t *acce
                      void *stream);
 
 /*
+ * Speculation-depth controller (paper Section 3.5, Eq. 8-16, Algorithm 4): host arithmetic only, no
+ * device work.  One ss_depth_state is the state of one stream of updates (the flow vector of the last h
+ * acceptance gradients, its write index, the smoothed throughput).  ss_depth_init fills a state with the
+ * paper's typical parameters (h 10, d_base 5, gamma 5, d_min 2, d_max 20, tau_target 400, tau_recent 0);
+ * the caller may then change the parameter fields.  ss_depth_update takes the metrics of the step just
+ * finished (accept_rate = accepted drafts / drafts in [0,1], load, throughput in tokens/s) and returns
+ * the clipped real depth d_star, the micro-batch size, the projected throughput, and k = the integer
+ * depth for the next verify step: floor(d_star + 1/2), at most SS_MAX_DEPTH.  Arithmetic is IEEE double.
+ * Where Algorithm 4 and the equations differ (which throughput scales and projects) the algorithm is
+ * followed: the `throughput` argument in both places.
+ * Errors: SS_ERR_INVALID_ARG (NULL state or output, h outside [1, SS_FLOW_MAX], NaN metrics).
+ */
+#define SS_FLOW_MAX 64
+typedef struct {
+    int32_t h;   /* history length */
+    int32_t idx; /* next slot of f to overwrite */
+    double f[SS_FLOW_MAX];
+    double d_base, gamma, d_min, d_max, tau_target, tau_recent;
+} ss_depth_state;
+
+int32_t ss_depth_init(ss_depth_state *state);
+int32_t ss_depth_update(ss_depth_state *state, double accept_rate, double load, double throughput, double *d_star,
+                        int32_t *b_micro, double *t_proj, int32_t *k);
+
+/*
  * Options (process-wide, not thread-safe; meant for tests and measurement).
  *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
  *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic

@@ -21,7 +21,8 @@ SS_OUT_WIDTH = 9
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_kv_append", "ss_kv_commit", "ss_set_option",
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_kv_append", "ss_kv_commit", "ss_depth_init",
+           "ss_depth_update", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
 
 
@@ -40,6 +41,15 @@ class ss_batch(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
                 ("max_q_len", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("block_table", ctypes.c_void_p), ("kv_len", ctypes.c_void_p), ("q_indptr", ctypes.c_void_p)]
+
+
+SS_FLOW_MAX = 64
+
+
+class ss_depth_state(ctypes.Structure):
+    _fields_ = [("h", ctypes.c_int32), ("idx", ctypes.c_int32), ("f", ctypes.c_double * SS_FLOW_MAX),
+                ("d_base", ctypes.c_double), ("gamma", ctypes.c_double), ("d_min", ctypes.c_double),
+                ("d_max", ctypes.c_double), ("tau_target", ctypes.c_double), ("tau_recent", ctypes.c_double)]
 
 
 _lib = None
@@ -75,6 +85,12 @@ def lib() -> ctypes.CDLL:
                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         L.ss_kv_commit.restype = ctypes.c_int32
         L.ss_kv_commit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.ss_depth_init.restype = ctypes.c_int32
+        L.ss_depth_init.argtypes = [ctypes.POINTER(ss_depth_state)]
+        L.ss_depth_update.restype = ctypes.c_int32
+        L.ss_depth_update.argtypes = [ctypes.POINTER(ss_depth_state), ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
         L.ss_set_option.restype = ctypes.c_int32
         L.ss_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
         L.ss_profile_begin.restype = ctypes.c_int32
@@ -198,6 +214,20 @@ def ss_kv_append(d: Dict[str, object]) -> None:
 def ss_kv_commit(q_indptr: torch.Tensor, accepted_len: torch.Tensor, kv_len: torch.Tensor) -> None:
     """Enqueue kv_len[b] <- kv_len[b] - k_b + accepted_len[b] on device int32 tensors (kv_len in place)."""
     _check(lib().ss_kv_commit(int(kv_len.numel()), _ptr(q_indptr), _ptr(accepted_len), _ptr(kv_len), _stream()))
+
+
+def ss_depth_init() -> ss_depth_state:
+    st = ss_depth_state()
+    _check(lib().ss_depth_init(ctypes.byref(st)))
+    return st
+
+
+def ss_depth_update(state: ss_depth_state, accept_rate: float, load: float, throughput: float):
+    """One controller step on the host; returns (d_star, b_micro, t_proj, k)."""
+    d, b, t, k = ctypes.c_double(), ctypes.c_int32(), ctypes.c_double(), ctypes.c_int32()
+    _check(lib().ss_depth_update(ctypes.byref(state), accept_rate, load, throughput, ctypes.byref(d), ctypes.byref(b),
+                                 ctypes.byref(t), ctypes.byref(k)))
+    return d.value, b.value, t.value, k.value
 
 
 def ss_spec_accept_workspace(batch: int, total_rows: int, vocab: int) -> int:

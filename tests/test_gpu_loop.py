@@ -74,3 +74,41 @@ def test_four_steps(oracle, base_cfg):
         want_len = oracle.kv_commit(q_indptr, n_used, step_in["kv_len"])
         assert np.array_equal(d["kv_len"].cpu().numpy(), want_len), f"step {step}: lengths after commit"
         cur = want_len
+
+
+def test_controller_closed_loop(oracle):
+    """Depths chosen by the controller from the acceptance each request just saw: the device loop
+    (ss_spec_accept + ss_depth_update) and the oracle loop must walk through the same depths."""
+    from oracle.depth_controller import DepthController
+    cfg = synth.CONFIGS[2].scaled(batch=12, vocab=2048)
+    B = cfg.batch
+    dev_state = [binding.ss_depth_init() for _ in range(B)]
+    ref_state = [DepthController() for _ in range(B)]
+    depth_dev = np.full(B, 5, dtype=np.int32)
+    depth_ref = depth_dev.copy()
+    seen = set()
+    for step in range(8):
+        assert np.array_equal(depth_dev, depth_ref), f"step {step}: depths diverged"
+        acc_in = synth.make_accept_inputs(cfg, seed=step, depth=depth_dev)
+        da = binding.accept_to_device(acc_in)
+        n_acc, toks, ratio, ws = binding.alloc_accept_outputs(da)
+        binding.ss_spec_accept(da, n_acc, toks, ratio, ws)
+        torch.cuda.synchronize()
+        g_n = n_acc.cpu().numpy()
+        ref = oracle.spec_accept(acc_in)
+        r_n = ref["accepted_len"].copy()
+        for b in range(B):
+            if g_n[b] != r_n[b]:    # only a flagged near-tie may differ; then follow the device
+                d0 = acc_in["q_indptr"][b] - b
+                assert ref["near_tie"][d0 + min(g_n[b], r_n[b])] == 1
+                r_n[b] = g_n[b]
+        load, tput = 0.2 + 0.05 * step, 150.0 + 60.0 * step
+        for b in range(B):
+            k = int(depth_dev[b])
+            a_dev = g_n[b] / k if k else 0.0
+            a_ref = r_n[b] / k if k else 0.0
+            depth_dev[b] = binding.ss_depth_update(dev_state[b], a_dev, load, tput)[3]
+            depth_ref[b] = ref_state[b].update(a_ref, load, tput)[3]
+            seen.add(int(depth_dev[b]))
+    assert np.array_equal(depth_dev, depth_ref)
+    assert len(seen) > 1, "the controller never moved the depth: the test exercises nothing"
