@@ -6,9 +6,13 @@
 // decide      one workgroup per request merges the chunk statistics of all its rows in parallel,
 //             evaluates u < p/q for every draft in fp64 and fixes the accepted length and the
 //             row(s) the new token is drawn from.
-// Passes 2a-2c touch only those one or two rows per request and work in fp64, so that the drawn
-// token can be reproduced by an fp64 reference: 2a normalisers per 2048-entry block, 2b residual
-// mass per block, 2c inverse-CDF search inside the block that holds u * mass.
+// Passes 2a-2b touch only those one or two rows per request and work in fp64, so that the drawn
+// token can be reproduced by an fp64 reference.  2a leaves, per 2048-entry block, the sums of the
+// unnormalised exponentials of both rows (the exact normalisers Zp, Zq once added up) and the same
+// sums restricted to the entries whose residual p - q is positive; which entries those are follows
+// from Zp/Zq as known from pass 1, except for entries within 1e-4 of the boundary, which are set
+// aside in a short list.  2b turns the sums into block masses P/Zp - Q/Zq, adds the listed entries
+// with the exact normalisers, and does the inverse-CDF search inside the block that holds u * mass.
 // All reductions have a fixed order (no atomics): results are run-to-run identical.
 #include "common.h"
 
@@ -28,14 +32,21 @@ struct RowPick {      // written by decide, read by the resampling passes
     float m_p, m_q;   // exact row maxima
     float temperature;
     int32_t n;        // accepted length
-    int32_t pad[2];
+    double rho;       // Zp/Zq as known from the fp32 row statistics (relative error below 2e-5)
 };
+
+constexpr int kAmbCap = 256;        // listed boundary entries per request; beyond that the slow exact path runs
+constexpr double kAmbEps = 1.0e-4;  // relative half-width of the boundary zone around p == q
 
 struct Workspace {
     float *cmax, *csum;   // [rows][nchunks]
     int32_t *carg;        // [rows][nchunks]
     RowPick *pick;        // [batch]
-    double *zp, *zq, *sc; // [batch][nsub]
+    double *zp, *zq, *sc; // [batch][nsub]: sums of exp over all entries of the block (p row, q row), block mass
+    double *pp, *qq;      // [batch][nsub]: the same sums over the entries with p clearly above q
+    int32_t *amb_cnt;     // [batch] entries in the boundary zone (may exceed kAmbCap: then the list is not used)
+    int32_t *amb_idx;     // [batch][kAmbCap] their vocabulary ids
+    double *amb_ep, *amb_eq;  // [batch][kAmbCap] their unnormalised exponentials
     int nchunks, nsub, rows;
 };
 
@@ -58,6 +69,13 @@ __host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
     w.zp = reinterpret_cast<double *>(p); p += perd;
     w.zq = reinterpret_cast<double *>(p); p += perd;
     w.sc = reinterpret_cast<double *>(p); p += perd;
+    w.pp = reinterpret_cast<double *>(p); p += perd;
+    w.qq = reinterpret_cast<double *>(p); p += perd;
+    const size_t pera = align_up(sizeof(double) * (size_t)batch * kAmbCap, 256);
+    w.amb_ep = reinterpret_cast<double *>(p); p += pera;
+    w.amb_eq = reinterpret_cast<double *>(p); p += pera;
+    w.amb_idx = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch * kAmbCap, 256);
+    w.amb_cnt = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch, 256);
     return w;
 }
 
@@ -333,37 +351,82 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
             pk.m_q = n < k ? row_m[k + 1 + n] : 0.f;
             pk.temperature = T;
             pk.n = n;
-            pk.pad[0] = pk.pad[1] = 0;
+            pk.rho = n < k ? row_z[n] / row_z[k + 1 + n] : 1.0;
             w.pick[b] = pk;
+            w.amb_cnt[b] = 0;
         }
     }
 }
 
-// ---- pass 2a: fp64 normalisers per block ----------------------------------------------------
+// ---- pass 2a: fp64 sums per block -------------------------------------------------------------
+// Four sums in one go (fixed order): lanes, then the four waves.
+__device__ __forceinline__ void block_sum4(double (&v)[4], double (*sh)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        for (int off = 32; off; off >>= 1) v[i] += __shfl_xor(v[i], off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sh[threadIdx.x >> 6][i] = v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (sh[0][i] + sh[1][i]) + (sh[2][i] + sh[3][i]);
+}
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
+    __shared__ double sh4[4][4];
     __shared__ ExpTable ex;
     ex.init();
     const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
     const RowPick pk = w.pick[b];
     const double inv_t = 1.0 / (double)pk.temperature;
+    const int64_t o = (int64_t)b * w.nsub + sub;
     float xp[kSubPer], xq[kSubPer];
     load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xp);
-    if (pk.q_row >= 0)
-        load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
-    double z = 0.0;
+    if (pk.q_row < 0) {   // bonus distribution: only the normaliser of the target row is needed
+        double z = 0.0;
 #pragma unroll
-    for (int s = 0; s < kSubPer; ++s) z += ex(((double)xp[s] - (double)pk.m_p) * inv_t);
-    z = block_sum<double>(z, sh);
-    if (tid == 0) w.zp[(int64_t)b * w.nsub + sub] = z;
-    if (pk.q_row < 0) return;
-    z = 0.0;
+        for (int s = 0; s < kSubPer; ++s) z += ex(((double)xp[s] - (double)pk.m_p) * inv_t);
+        z = block_sum<double>(z, sh);
+        if (tid == 0) w.zp[o] = z;
+        return;
+    }
+    load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
+    // v[0], v[1]: exponentials of all entries (p row, q row); v[2], v[3]: of the entries whose residual
+    // p - q is positive for certain, i.e. ep / eq above rho by more than the boundary zone
+    double v[4] = {0.0, 0.0, 0.0, 0.0};
+    const double hi = pk.rho * (1.0 + kAmbEps), lo = pk.rho * (1.0 - kAmbEps);
 #pragma unroll
-    for (int s = 0; s < kSubPer; ++s) z += ex(((double)xq[s] - (double)pk.m_q) * inv_t);
-    z = block_sum<double>(z, sh);
-    if (tid == 0) w.zq[(int64_t)b * w.nsub + sub] = z;
+    for (int s = 0; s < kSubPer; ++s) {
+        const double ep = ex(((double)xp[s] - (double)pk.m_p) * inv_t);
+        const double eq = ex(((double)xq[s] - (double)pk.m_q) * inv_t);
+        v[0] += ep;
+        v[1] += eq;
+        if (ep > hi * eq) {
+            v[2] += ep;
+            v[3] += eq;
+        } else if (ep > 0.0 && ep >= lo * eq) {   // too close to call before Zp/Zq are exact: list it
+            const int slot = atomicAdd(&w.amb_cnt[b], 1);
+            if (slot < kAmbCap) {
+                const int64_t l = (int64_t)b * kAmbCap + slot;
+                w.amb_idx[l] = index_of<DT, kSubPer, false>(sub * kSub, tid, s);
+                w.amb_ep[l] = ep;
+                w.amb_eq[l] = eq;
+            }
+        }
+    }
+    block_sum4(v, sh4);
+    if (tid == 0) {
+        w.zp[o] = v[0];
+        w.zq[o] = v[1];
+        w.pp[o] = v[2];
+        w.qq[o] = v[3];
+    }
 }
 
 // Sum of v[0..n) with a fixed association (lane-strided partial sums, then the block tree): every
@@ -385,33 +448,7 @@ __device__ __forceinline__ double mass(const ExpTable &ex, float lp, float lq, c
     return p > q ? p - q : 0.0;
 }
 
-// ---- pass 2b: residual mass per block -------------------------------------------------------
-template <int DT>
-__global__ __launch_bounds__(kThreads) void accept_mass_kernel(AcceptArgs a, Workspace w)
-{
-    __shared__ double sh[4];
-    __shared__ ExpTable ex;
-    const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
-    const RowPick pk = w.pick[b];
-    const double zp = block_total(w.zp + (int64_t)b * w.nsub, w.nsub, sh);
-    if (pk.q_row < 0) {  // bonus distribution: the block's share of p
-        if (tid == 0) w.sc[(int64_t)b * w.nsub + sub] = w.zp[(int64_t)b * w.nsub + sub] / zp;
-        return;
-    }
-    ex.init();
-    float xp[kSubPer], xq[kSubPer];
-    load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xp);
-    load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
-    const double zq = block_total(w.zq + (int64_t)b * w.nsub, w.nsub, sh);
-    const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
-    double s = 0.0;
-#pragma unroll
-    for (int i = 0; i < kSubPer; ++i) s += mass(ex, xp[i], xq[i], pk, inv_t, inv_zp, inv_zq);
-    s = block_sum<double>(s, sh);
-    if (tid == 0) w.sc[(int64_t)b * w.nsub + sub] = s;
-}
-
-// ---- pass 2c: inverse-CDF search ------------------------------------------------------------
+// ---- pass 2b: block masses and inverse-CDF search ------------------------------------------------------------
 template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Workspace w)
 {
@@ -422,7 +459,83 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowPick pk = w.pick[b];
     int32_t *dst = a.out_tokens + (int64_t)b * SS_OUT_WIDTH + pk.n;
-    const double *sc = w.sc + (int64_t)b * w.nsub;
+    // block masses live in LDS unless the vocabulary has more blocks than fit there
+    constexpr int kScCap = 1024;
+    __shared__ double sc_sh[kScCap];
+    __shared__ double sh4[4][4];
+    double *sc = w.nsub <= kScCap ? sc_sh : w.sc + (int64_t)b * w.nsub;
+    const int64_t ob = (int64_t)b * w.nsub;
+    // everything that does not depend on anything else is requested up front
+    const float u_s = a.u_sample[b];
+    const int namb = pk.q_row >= 0 ? w.amb_cnt[b] : 0;
+    const bool own = tid < w.nsub;
+    const double zp0 = own ? w.zp[ob + tid] : 0.0;
+    const double zq0 = own && pk.q_row >= 0 ? w.zq[ob + tid] : 0.0;
+    const double pp0 = own && pk.q_row >= 0 ? w.pp[ob + tid] : 0.0;
+    const double qq0 = own && pk.q_row >= 0 ? w.qq[ob + tid] : 0.0;
+    ex.init();
+
+    // exact normalisers, then the mass of every block
+    double tot[4] = {zp0, zq0, 0.0, 0.0};
+    for (int c = tid + kThreads; c < w.nsub; c += kThreads) {
+        tot[0] += w.zp[ob + c];
+        if (pk.q_row >= 0) tot[1] += w.zq[ob + c];
+    }
+    block_sum4(tot, sh4);
+    const double zp = tot[0], zq = pk.q_row >= 0 ? tot[1] : 1.0;
+    const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
+    if (pk.q_row < 0) {
+        if (own) sc[tid] = zp0 / zp;
+        for (int c = tid + kThreads; c < w.nsub; c += kThreads) sc[c] = w.zp[ob + c] / zp;
+    } else if (namb <= kAmbCap) {
+        if (own) {
+            const double m = pp0 * inv_zp - qq0 * inv_zq;
+            sc[tid] = m > 0.0 ? m : 0.0;
+        }
+        for (int c = tid + kThreads; c < w.nsub; c += kThreads) {
+            const double m = w.pp[ob + c] * inv_zp - w.qq[ob + c] * inv_zq;
+            sc[c] = m > 0.0 ? m : 0.0;
+        }
+        if (namb > 0) {
+            // The listed boundary entries, now that Zp and Zq are exact.  They arrive in no particular
+            // order: rank them by vocabulary id so that every block's additions happen in a fixed order.
+            __shared__ int amb_id[kAmbCap], amb_blk[kAmbCap];
+            __shared__ double amb_r[kAmbCap];
+            for (int e = tid; e < namb; e += kThreads) amb_id[e] = w.amb_idx[(int64_t)b * kAmbCap + e];
+            __syncthreads();
+            for (int e = tid; e < namb; e += kThreads) {
+                const int64_t l = (int64_t)b * kAmbCap + e;
+                const int id = amb_id[e];
+                int rank = 0;
+                for (int f = 0; f < namb; ++f) rank += amb_id[f] < id;
+                const double r = w.amb_ep[l] * inv_zp - w.amb_eq[l] * inv_zq;
+                amb_blk[rank] = id / kSub;
+                amb_r[rank] = r > 0.0 ? r : 0.0;
+            }
+            __syncthreads();
+            for (int e = tid; e < namb; e += kThreads) {
+                if (e == 0 || amb_blk[e - 1] != amb_blk[e]) {   // first listed entry of its block: add the block's run
+                    double add = 0.0;
+                    for (int f = e; f < namb && amb_blk[f] == amb_blk[e]; ++f) add += amb_r[f];
+                    sc[amb_blk[e]] += add;
+                }
+            }
+        }
+    } else {
+        // Too many entries near p == q to list (rows that nearly coincide): every block's mass entry by entry.
+        for (int c = 0; c < w.nsub; ++c) {
+            float yp[kSubPer], yq[kSubPer];
+            load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, c * kSub, tid, yp);
+            load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, c * kSub, tid, yq);
+            double m = 0.0;
+#pragma unroll
+            for (int i = 0; i < kSubPer; ++i) m += mass(ex, yp[i], yq[i], pk, inv_t, inv_zp, inv_zq);
+            m = block_sum<double>(m, wave_tot);
+            if (tid == 0) sc[c] = m;
+        }
+    }
+    __threadfence_block();
+    __syncthreads();
 
     // Inclusive scan of the block masses in index order (lane c holds block c; vocabularies beyond
     // 256 blocks take several rounds), first for the total S, then again to find the first block
@@ -434,7 +547,7 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     int cand = 0x7fffffff, last = -1;
     double cand_prefix = 0.0, last_prefix = 0.0;
     for (int pass = 0; pass < 2; ++pass) {
-        const double thr0 = (double)a.u_sample[b] * S;
+        const double thr0 = (double)u_s * S;
         __syncthreads();
         if (tid == 0) { carry_sh = 0.0; cstar_sh = 0x7fffffff; lastpos_sh = -1; }
         __syncthreads();
@@ -485,13 +598,9 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     const int cstar = take_last ? lastpos_sh : cstar_sh;
     if (!take_last && cand == cstar) prefix_sh = cand_prefix;
     if (take_last && last == cstar) prefix_sh = last_prefix;
-    ex.init();   // (contains the barrier that publishes prefix_sh)
-    const double thr = (double)a.u_sample[b] * S;
+    __syncthreads();   // publishes prefix_sh
+    const double thr = (double)u_s * S;
     const double prefix = prefix_sh;
-
-    const double zp = block_total(w.zp + (int64_t)b * w.nsub, w.nsub, wave_tot);
-    const double zq = pk.q_row >= 0 ? block_total(w.zq + (int64_t)b * w.nsub, w.nsub, wave_tot) : 1.0;
-    const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
     float xp[kSubPer], xq[kSubPer];
     load_slots<DT, kSubPer, true>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, cstar * kSub, tid, xp);
     if (pk.q_row >= 0)
@@ -557,7 +666,10 @@ size_t accept_workspace_bytes(int batch, int total_rows, int vocab)
     const size_t rows = 2 * (size_t)total_rows - batch;
     size_t n = 3 * align_up(sizeof(float) * rows * nch, 256);
     n += align_up(sizeof(RowPick) * (size_t)batch, 256);
-    n += 3 * align_up(sizeof(double) * (size_t)batch * nsub, 256);
+    n += 5 * align_up(sizeof(double) * (size_t)batch * nsub, 256);
+    n += 2 * align_up(sizeof(double) * (size_t)batch * kAmbCap, 256);
+    n += align_up(sizeof(int32_t) * (size_t)batch * kAmbCap, 256);
+    n += align_up(sizeof(int32_t) * (size_t)batch, 256);
     return n + 256;
 }
 
@@ -571,8 +683,6 @@ static int32_t accept_launch_dt(const AcceptArgs &a, const Workspace &w, unsigne
     if (a.greedy) return SS_OK;
     hipLaunchKernelGGL(accept_norm_kernel<DT>, dim3(g2), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_norm_kernel");
-    hipLaunchKernelGGL(accept_mass_kernel<DT>, dim3(g2), dim3(kThreads), 0, stream, a, w);
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_mass_kernel");
     hipLaunchKernelGGL(accept_pick_kernel<DT>, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_pick_kernel");
     return SS_OK;

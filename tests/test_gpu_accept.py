@@ -133,6 +133,29 @@ def test_special_cases(oracle):
     del rng
 
 
+def test_nearly_coincident_rows(oracle):
+    # Draft rows that equal the target rows except for a handful of entries: almost every entry sits in
+    # the zone where the sign of p - q cannot be told before the exact normalisers are known, the
+    # residual is tiny, and a forced rejection has to draw from it.  Exercises the exact slow path of
+    # the residual masses (far more boundary entries than the short list holds) and, with a larger
+    # perturbation, the list itself.
+    B, V, k = 12, 40000, 2
+    cfg = LLAMA8B.scaled(batch=B, vocab=V, depth=("fixed", k))
+    for n_changed, shift in ((5, 0.5), (3000, 0.125), (V // 2, 2.0)):
+        inp = synth.make_accept_inputs(cfg, seed=11)
+        rows = np.concatenate([np.arange(inp["q_indptr"][b], inp["q_indptr"][b] + k) for b in range(B)])
+        drf = synth.decode_storage(np.ascontiguousarray(inp["target_logits"][rows]), "bf16").astype(np.float32)
+        rng = np.random.default_rng(n_changed)
+        for r in range(drf.shape[0]):
+            ids = rng.choice(V, n_changed, replace=False)
+            drf[r, ids] += np.float32(shift) * rng.choice([-1.0, 1.0], n_changed).astype(np.float32)
+        d = dict(inp)
+        d["draft_logits"] = np.zeros_like(inp["draft_logits"])
+        d["draft_logits"][:, :V] = synth.store(drf, "bf16")
+        d["u_accept"] = np.full_like(inp["u_accept"], np.float32(0.9999999))   # reject wherever p/q < 1
+        compare(d, oracle, label=f"nearly coincident rows, {n_changed} entries moved")
+
+
 def test_depth_zero_only(oracle):
     cfg = LLAMA8B.scaled(batch=8, vocab=128256, depth=("fixed", 0))
     inp = synth.make_accept_inputs(cfg, seed=4)
