@@ -215,60 +215,137 @@ struct ExpTable {
 };
 
 // ---- pass 1 ---------------------------------------------------------------------------------
-// grid: batch * kMaxRows * nchunks; workgroup (b, j, chunk) handles chunk `chunk` of request b's row j
-// (j <= k: target row j; k < j <= 2k: draft row j-k-1; larger j: nothing to do).
+// grid: batch * kMaxRows * ceil(nchunks / 4); workgroup (b, j, group): wave wv of it streams chunk
+// 4 * group + wv of request b's row j (j <= k: target row j; k < j <= 2k: draft row j-k-1; larger j:
+// nothing to do).  A wave owns its chunk alone: all of its 16-byte loads go out first, then the
+// values are folded vector by vector into a per-lane running (max, sum) and reduced across the wave
+// with shuffles, so the streaming pass has no barrier and no LDS traffic.
+template <int DT>
+__device__ __forceinline__ void unpack(const uint4 &w, float (&x)[DT == SS_BF16 ? 8 : 4])
+{
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if constexpr (DT == SS_BF16) {
+            x[2 * j] = __uint_as_float(ww[j] << 16);
+            x[2 * j + 1] = __uint_as_float(ww[j] & 0xffff0000u);
+        } else {
+            x[j] = __uint_as_float(ww[j]);
+        }
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a, Workspace w)
 {
-    __shared__ float sh[4];
-    __shared__ int shi[4];
-    const int chunk = blockIdx.x % w.nchunks, tid = threadIdx.x;
-    const int bj = blockIdx.x / w.nchunks, b = bj / kMaxRows, j = bj % kMaxRows;
+    constexpr int vec = DT == SS_BF16 ? 8 : 4;       // logits per 16-byte load
+    constexpr int NV = kChunk / (64 * vec);          // loads per lane and chunk
+    constexpr int STEP = 4;                          // vectors folded per update of the running maximum
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int groups = (w.nchunks + 3) / 4;
+    const int chunk = (blockIdx.x % groups) * 4 + wv;
+    const int bj = blockIdx.x / groups, b = bj / kMaxRows, j = bj % kMaxRows;
     const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1;
-    if (j > (a.greedy ? k : 2 * k)) return;
+    if (j > (a.greedy ? k : 2 * k) || chunk >= w.nchunks) return;
     const bool is_draft = j > k;
     const int r = is_draft ? t0 - b + (j - k - 1) : t0 + j;
     const int64_t ry = is_draft ? (int64_t)a.total_rows + r : r;
     const void *row = row_ptr(is_draft ? a.draft : a.target, r, a.row_stride, DT);
-    float x[kPerThread];
-    load_slots<DT, kPerThread, false>(row, a.vocab, chunk * kChunk, tid, x);
-
-    float m = x[0];
-#pragma unroll
-    for (int s = 1; s < kPerThread; ++s) m = fmaxf(m, x[s]);
+    const int base = chunk * kChunk;
     const int64_t o = ry * w.nchunks + chunk;
-    if (a.greedy) {
-        const float cm = block_max(m, sh);
-        // lowest vocabulary id holding the chunk maximum
-        int best = 0x7fffffff;
+    const float T = a.greedy ? 1.f : (a.temperature ? a.temperature[b] : a.temperature_scalar);
+    const float sc = 1.4426950408889634f / T;
+
+    // vector v of this lane starts at vocabulary id base + v * (64 * vec) + lane * vec
+    uint4 raw[NV];
+    const bool full = base + kChunk <= a.vocab;       // uniform: the chunk lies inside the vocabulary
+    const int last_full = a.vocab >= vec ? (a.vocab - vec) / vec * vec : -1;
+    if (full) {
 #pragma unroll
-        for (int s = 0; s < kPerThread; ++s) {
-            const int id = index_of<DT, kPerThread, false>(chunk * kChunk, tid, s);
-            if (x[s] == cm && id < best) best = id;
+        for (int v = 0; v < NV; ++v) {
+            const int i0 = base + v * (64 * vec) + lane * vec;
+            raw[v] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(row) + (int64_t)i0 * (DT == SS_BF16 ? 2 : 4));
         }
-        for (int off = 32; off; off >>= 1) best = min(best, __shfl_xor(best, off));
-        __syncthreads();
-        if ((tid & 63) == 0) shi[tid >> 6] = best;
-        __syncthreads();
-        if (tid == 0) {
+    } else {
+        // the chunk that holds the end of the vocabulary: loads from a clamped, in-bounds address
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int i0 = base + v * (64 * vec) + lane * vec;
+            const int ic = i0 < last_full ? i0 : last_full;
+            raw[v] = make_uint4(0, 0, 0, 0);
+            if (last_full >= 0)
+                raw[v] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(row) + (int64_t)ic * (DT == SS_BF16 ? 2 : 4));
+        }
+    }
+
+    float m = -INFINITY, z = 0.f;
+    int best = 0x7fffffff;
+#pragma unroll
+    for (int s0 = 0; s0 < NV; s0 += STEP) {
+        float x[STEP][vec];
+#pragma unroll
+        for (int v = 0; v < STEP; ++v) {
+            unpack<DT>(raw[s0 + v], x[v]);
+            if (!full) {
+                const int i0 = base + (s0 + v) * (64 * vec) + lane * vec;
+                if (i0 + vec > a.vocab) {   // past the end, or the one vector that straddles it
+#pragma unroll
+                    for (int e = 0; e < vec; ++e) {
+                        float val = -INFINITY;
+                        if (i0 + e < a.vocab) {
+                            if constexpr (DT == SS_BF16)
+                                val = __uint_as_float((uint32_t) static_cast<const uint16_t *>(row)[i0 + e] << 16);
+                            else
+                                val = static_cast<const float *>(row)[i0 + e];
+                        }
+                        x[v][e] = val;
+                    }
+                }
+            }
+        }
+        float mx = x[0][0];
+#pragma unroll
+        for (int v = 0; v < STEP; ++v)
+#pragma unroll
+            for (int e = 0; e < vec; ++e) mx = fmaxf(mx, x[v][e]);
+        if (a.greedy) {
+            if (mx > m) {   // a new maximum: its first position within this step, ids ascend with (v, e)
+                m = mx;
+                best = 0x7fffffff;
+#pragma unroll
+                for (int v = STEP - 1; v >= 0; --v)
+#pragma unroll
+                    for (int e = vec - 1; e >= 0; --e)
+                        if (x[v][e] == mx) best = base + (s0 + v) * (64 * vec) + lane * vec + e;
+            }
+        } else {
+            const float m_new = fmaxf(m, mx);
+            if (m_new != -INFINITY) {
+                float acc = 0.f;
+#pragma unroll
+                for (int v = 0; v < STEP; ++v)
+#pragma unroll
+                    for (int e = 0; e < vec; ++e) acc += __builtin_amdgcn_exp2f((x[v][e] - m_new) * sc);
+                z = z * __builtin_amdgcn_exp2f((m - m_new) * sc) + acc;   // m == -inf: z is 0 and the factor 0
+                m = m_new;
+            }
+        }
+    }
+    // across the wave
+    float cm = m;
+    for (int off = 32; off; off >>= 1) cm = fmaxf(cm, __shfl_xor(cm, off));
+    if (a.greedy) {
+        int arg = m == cm ? best : 0x7fffffff;   // lowest vocabulary id holding the chunk maximum
+        for (int off = 32; off; off >>= 1) arg = min(arg, __shfl_xor(arg, off));
+        if (lane == 0) {
             w.cmax[o] = cm;
-            w.carg[o] = min(min(shi[0], shi[1]), min(shi[2], shi[3]));
+            w.carg[o] = arg;
         }
         return;
     }
-    // each lane sums its exponentials against its own maximum first (no barrier before the
-    // transcendental work), the 256 (max, sum) pairs are combined afterwards
-    const float T = a.temperature ? a.temperature[b] : a.temperature_scalar;
-    const float sc = 1.4426950408889634f / T;
-    float z = 0.f;
-    if (m != -INFINITY) {
-#pragma unroll
-        for (int s = 0; s < kPerThread; ++s) z += __builtin_amdgcn_exp2f((x[s] - m) * sc);
-    }
-    const float cm = block_max(m, sh);
     if (m != -INFINITY) z *= __builtin_amdgcn_exp2f((m - cm) * sc);
-    z = block_sum<float>(z, sh);
-    if (tid == 0) {
+    for (int off = 32; off; off >>= 1) z += __shfl_xor(z, off);
+    if (lane == 0) {
         w.cmax[o] = cm;
         w.csum[o] = z;
     }
@@ -691,7 +768,7 @@ static int32_t accept_launch_dt(const AcceptArgs &a, const Workspace &w, unsigne
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
 {
     const Workspace w = carve(a.workspace, a.batch, a.total_rows, a.vocab);
-    const unsigned long long g1 = (unsigned long long)a.batch * kMaxRows * w.nchunks;
+    const unsigned long long g1 = (unsigned long long)a.batch * kMaxRows * ((w.nchunks + 3) / 4);
     const unsigned long long g2 = (unsigned long long)a.batch * w.nsub;
     if (g1 > 0x7fffffffull || g2 > 0x7fffffffull)
         return fail(SS_ERR_UNSUPPORTED, "batch * vocab too large for one launch");
