@@ -224,6 +224,26 @@ int32_t ss_depth_update(ss_depth_state *state, double accept_rate, double load, 
                         int32_t *b_micro, double *t_proj, int32_t *k);
 
 /*
+ * Router worker selection (paper Section 3.2, Eq. 1-4, Algorithm 2): host arithmetic only.  Worker i
+ * reports cache hit rate, memory utilisation and active load in [0,1], its queue depth, and whether its
+ * metrics are stale.  A worker is eligible if it is not stale and its overload score
+ * mem + 2 * depth / q_max does not exceed tau (Eq. 2, 3; the memory term of Eq. 3 is the paper's
+ * "per cent / 100", i.e. the same number in [0,1]).  Among the eligible workers the one with the highest
+ * score alpha[0]*cache + alpha[1]*(1-mem) + alpha[2]*(1-min(depth/q_max,1)) + alpha[3]*(1-load) is chosen
+ * (Eq. 1); if none is eligible, the worker with the smallest queue depth among all (Eq. 4).  Ties go to
+ * the lowest index.  alpha == NULL takes the paper's weights (0.4, 0.1, 0.3, 0.2); tau <= 0 takes 0.85.
+ * Arithmetic is IEEE double.  Errors: SS_ERR_INVALID_ARG (n <= 0, NULL workers/chosen, q_max <= 0).
+ */
+typedef struct {
+    double cache_hit, mem, load;
+    int32_t queue_depth;
+    int32_t stale;
+} ss_worker_metrics;
+
+int32_t ss_route_select(const ss_worker_metrics *workers, int32_t n, const double *alpha, double tau, double q_max,
+                        int32_t *chosen);
+
+/*
  * Options (process-wide, not thread-safe; meant for tests and measurement).
  *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
  *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic

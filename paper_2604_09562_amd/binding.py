@@ -22,7 +22,7 @@ _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
            "ss_spec_accept_workspace", "ss_spec_accept", "ss_kv_append", "ss_kv_commit", "ss_depth_init",
-           "ss_depth_update", "ss_set_option",
+           "ss_depth_update", "ss_route_select", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
 
 
@@ -50,6 +50,11 @@ class ss_depth_state(ctypes.Structure):
     _fields_ = [("h", ctypes.c_int32), ("idx", ctypes.c_int32), ("f", ctypes.c_double * SS_FLOW_MAX),
                 ("d_base", ctypes.c_double), ("gamma", ctypes.c_double), ("d_min", ctypes.c_double),
                 ("d_max", ctypes.c_double), ("tau_target", ctypes.c_double), ("tau_recent", ctypes.c_double)]
+
+
+class ss_worker_metrics(ctypes.Structure):
+    _fields_ = [("cache_hit", ctypes.c_double), ("mem", ctypes.c_double), ("load", ctypes.c_double),
+                ("queue_depth", ctypes.c_int32), ("stale", ctypes.c_int32)]
 
 
 _lib = None
@@ -91,6 +96,9 @@ def lib() -> ctypes.CDLL:
         L.ss_depth_update.argtypes = [ctypes.POINTER(ss_depth_state), ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
+        L.ss_route_select.restype = ctypes.c_int32
+        L.ss_route_select.argtypes = [ctypes.POINTER(ss_worker_metrics), ctypes.c_int32, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_int32)]
         L.ss_set_option.restype = ctypes.c_int32
         L.ss_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
         L.ss_profile_begin.restype = ctypes.c_int32
@@ -228,6 +236,17 @@ def ss_depth_update(state: ss_depth_state, accept_rate: float, load: float, thro
     _check(lib().ss_depth_update(ctypes.byref(state), accept_rate, load, throughput, ctypes.byref(d), ctypes.byref(b),
                                  ctypes.byref(t), ctypes.byref(k)))
     return d.value, b.value, t.value, k.value
+
+
+def ss_route_select(workers, q_max: float, alpha=None, tau: float = 0.0) -> int:
+    """workers: sequence of (cache_hit, mem, queue_depth, load, stale).  Returns the chosen index."""
+    arr = (ss_worker_metrics * len(workers))()
+    for i, (c, m, d, l, st) in enumerate(workers):
+        arr[i] = ss_worker_metrics(c, m, l, int(d), int(bool(st)))
+    al = None if alpha is None else (ctypes.c_double * 4)(*alpha)
+    out = ctypes.c_int32(-1)
+    _check(lib().ss_route_select(arr, len(workers), al, tau, q_max, ctypes.byref(out)))
+    return out.value
 
 
 def ss_spec_accept_workspace(batch: int, total_rows: int, vocab: int) -> int:
