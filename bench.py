@@ -5,7 +5,7 @@ One "step" = one pass of the whole hot path over one synthetic batch: the KV
 plan, the KV-streaming attention kernel, the partial merge, and the five accept
 passes.  Inputs are resident in HBM before the timed region; several copies of
 the cache and logits are rotated so the last-level cache cannot serve the stream.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (verified tokens/s), roofline of the KV-streaming kernel, CPU-oracle baseline.
 """
 from __future__ import annotations
 
