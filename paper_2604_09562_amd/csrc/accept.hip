@@ -11,8 +11,9 @@
 // unnormalised exponentials of both rows (the exact normalisers Zp, Zq once added up) and the same
 // sums restricted to the entries whose residual p - q is positive; which entries those are follows
 // from Zp/Zq as known from pass 1, except for entries within 1e-4 of the boundary, which are set
-// aside in a short list.  2b turns the sums into block masses P/Zp - Q/Zq, adds the listed entries
-// with the exact normalisers, and does the inverse-CDF search inside the block that holds u * mass.
+// aside in a list (each block's entries contiguous).  2b turns the sums into block masses
+// P/Zp - Q/Zq, adds the listed entries with the exact normalisers, and does the inverse-CDF search
+// inside the block that holds u * mass.
 // All reductions have a fixed order (no atomics): results are run-to-run identical.
 #include "common.h"
 
@@ -35,8 +36,9 @@ struct RowPick {      // written by decide, read by the resampling passes
     double rho;       // Zp/Zq as known from the fp32 row statistics (relative error below 2e-5)
 };
 
-constexpr int kAmbCap = 256;        // listed boundary entries per request; beyond that the slow exact path runs
+constexpr int kAmbCap = 4096;       // listed boundary entries per request; beyond that the slow exact path runs
 constexpr double kAmbEps = 1.0e-4;  // relative half-width of the boundary zone around p == q
+constexpr int kPickWgs = 8;         // workgroups per request in the last pass (all but one idle unless the list overflowed)
 
 struct Workspace {
     float *cmax, *csum;   // [rows][nchunks]
@@ -45,8 +47,9 @@ struct Workspace {
     double *zp, *zq, *sc; // [batch][nsub]: sums of exp over all entries of the block (p row, q row), block mass
     double *pp, *qq;      // [batch][nsub]: the same sums over the entries with p clearly above q
     int32_t *amb_cnt;     // [batch] entries in the boundary zone (may exceed kAmbCap: then the list is not used)
-    int32_t *amb_idx;     // [batch][kAmbCap] their vocabulary ids
-    double *amb_ep, *amb_eq;  // [batch][kAmbCap] their unnormalised exponentials
+    int32_t *done;        // [batch] workgroups of the last pass that have delivered their block masses
+    int32_t *blk_base, *blk_cnt;  // [batch][nsub] where in the list a block's entries start, and how many they are
+    double *amb_ep, *amb_eq;  // [batch][kAmbCap] their unnormalised exponentials, each block's entries contiguous
     int nchunks, nsub, rows;
 };
 
@@ -74,8 +77,11 @@ __host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
     const size_t pera = align_up(sizeof(double) * (size_t)batch * kAmbCap, 256);
     w.amb_ep = reinterpret_cast<double *>(p); p += pera;
     w.amb_eq = reinterpret_cast<double *>(p); p += pera;
-    w.amb_idx = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch * kAmbCap, 256);
+    const size_t peri = align_up(sizeof(int32_t) * (size_t)batch * w.nsub, 256);
+    w.blk_base = reinterpret_cast<int32_t *>(p); p += peri;
+    w.blk_cnt = reinterpret_cast<int32_t *>(p); p += peri;
     w.amb_cnt = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch, 256);
+    w.done = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch, 256);
     return w;
 }
 
@@ -431,32 +437,34 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
             pk.rho = n < k ? row_z[n] / row_z[k + 1 + n] : 1.0;
             w.pick[b] = pk;
             w.amb_cnt[b] = 0;
+            w.done[b] = 0;
         }
     }
 }
 
 // ---- pass 2a: fp64 sums per block -------------------------------------------------------------
-// Four sums in one go (fixed order): lanes, then the four waves.
-__device__ __forceinline__ void block_sum4(double (&v)[4], double (*sh)[4])
+// N sums in one go (fixed order): lanes, then the four waves.
+template <int N>
+__device__ __forceinline__ void block_sums(double (&v)[N], double (*sh)[N])
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < N; ++i)
         for (int off = 32; off; off >>= 1) v[i] += __shfl_xor(v[i], off);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sh[threadIdx.x >> 6][i] = v[i];
+        for (int i = 0; i < N; ++i) sh[threadIdx.x >> 6][i] = v[i];
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = (sh[0][i] + sh[1][i]) + (sh[2][i] + sh[3][i]);
+    for (int i = 0; i < N; ++i) v[i] = (sh[0][i] + sh[1][i]) + (sh[2][i] + sh[3][i]);
 }
 
 template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ double sh[4];
-    __shared__ double sh4[4][4];
+    __shared__ double sh5[4][5];
     __shared__ ExpTable ex;
     ex.init();
     const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
@@ -476,8 +484,9 @@ __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Wor
     load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, sub * kSub, tid, xq);
     // v[0], v[1]: exponentials of all entries (p row, q row); v[2], v[3]: of the entries whose residual
     // p - q is positive for certain, i.e. ep / eq above rho by more than the boundary zone
-    double v[4] = {0.0, 0.0, 0.0, 0.0};
+    double v[5] = {0.0, 0.0, 0.0, 0.0, 0.0};   // [4]: how many entries of the block are too close to call
     const double hi = pk.rho * (1.0 + kAmbEps), lo = pk.rho * (1.0 - kAmbEps);
+    unsigned near = 0;   // slots of this lane that are too close to call before Zp/Zq are exact
 #pragma unroll
     for (int s = 0; s < kSubPer; ++s) {
         const double ep = ex(((double)xp[s] - (double)pk.m_p) * inv_t);
@@ -487,22 +496,54 @@ __global__ __launch_bounds__(kThreads) void accept_norm_kernel(AcceptArgs a, Wor
         if (ep > hi * eq) {
             v[2] += ep;
             v[3] += eq;
-        } else if (ep > 0.0 && ep >= lo * eq) {   // too close to call before Zp/Zq are exact: list it
-            const int slot = atomicAdd(&w.amb_cnt[b], 1);
-            if (slot < kAmbCap) {
-                const int64_t l = (int64_t)b * kAmbCap + slot;
-                w.amb_idx[l] = index_of<DT, kSubPer, false>(sub * kSub, tid, s);
-                w.amb_ep[l] = ep;
-                w.amb_eq[l] = eq;
-            }
+        } else if (ep > 0.0 && ep >= lo * eq) {
+            near |= 1u << s;
         }
     }
-    block_sum4(v, sh4);
+    // The boundary entries of this block go to the request's list as one contiguous run, in lane and
+    // slot order (so their later additions have a fixed order); one counter update per block.
+    __shared__ int wave_cnt[4], run_base;
+    const int mine = __popc(near);
+    v[4] = (double)mine;
+    block_sums<5>(v, sh5);
+    const int total = (int)v[4];
     if (tid == 0) {
         w.zp[o] = v[0];
         w.zq[o] = v[1];
         w.pp[o] = v[2];
         w.qq[o] = v[3];
+        w.blk_cnt[o] = total;
+    }
+    if (total > 0) {
+        int incl = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off);
+            if ((tid & 63) >= off) incl += t;
+        }
+        if ((tid & 63) == 63) wave_cnt[tid >> 6] = incl;
+        __syncthreads();
+        int before = 0;
+        for (int wv = 0; wv < (tid >> 6); ++wv) before += wave_cnt[wv];
+        if (tid == 0) {
+            run_base = atomicAdd(&w.amb_cnt[b], total);
+            w.blk_base[o] = run_base;
+        }
+        __syncthreads();
+        if (run_base + total <= kAmbCap) {
+            int64_t l = (int64_t)b * kAmbCap + run_base + before + (incl - mine);
+#pragma unroll
+            for (int s = 0; s < kSubPer; ++s) {
+                if (near & (1u << s)) {
+                    // evaluated again rather than kept (the same bits): keeping sixteen doubles per lane
+                    // alive for this rare branch would halve the kernel's occupancy
+                    float yp = xp[s], yq = xq[s];
+                    asm volatile("" : "+v"(yp), "+v"(yq));
+                    w.amb_ep[l] = ex(((double)yp - (double)pk.m_p) * inv_t);
+                    w.amb_eq[l] = ex(((double)yq - (double)pk.m_q) * inv_t);
+                    ++l;
+                }
+            }
+        }
     }
 }
 
@@ -533,18 +574,21 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     __shared__ int sh_first[4], sh_last[4];
     __shared__ float sh_f[4];
     __shared__ ExpTable ex;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x / kPickWgs, part = blockIdx.x % kPickWgs;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowPick pk = w.pick[b];
     int32_t *dst = a.out_tokens + (int64_t)b * SS_OUT_WIDTH + pk.n;
     // block masses live in LDS unless the vocabulary has more blocks than fit there
     constexpr int kScCap = 1024;
     __shared__ double sc_sh[kScCap];
     __shared__ double sh4[4][4];
-    double *sc = w.nsub <= kScCap ? sc_sh : w.sc + (int64_t)b * w.nsub;
     const int64_t ob = (int64_t)b * w.nsub;
     // everything that does not depend on anything else is requested up front
     const float u_s = a.u_sample[b];
     const int namb = pk.q_row >= 0 ? w.amb_cnt[b] : 0;
+    const bool listed = namb <= kAmbCap;
+    if (listed && part != 0) return;   // one workgroup does the whole request unless the list overflowed
+    double *sc = listed && w.nsub <= kScCap ? sc_sh : w.sc + ob;
     const bool own = tid < w.nsub;
     const double zp0 = own ? w.zp[ob + tid] : 0.0;
     const double zq0 = own && pk.q_row >= 0 ? w.zq[ob + tid] : 0.0;
@@ -558,13 +602,13 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
         tot[0] += w.zp[ob + c];
         if (pk.q_row >= 0) tot[1] += w.zq[ob + c];
     }
-    block_sum4(tot, sh4);
+    block_sums<4>(tot, sh4);
     const double zp = tot[0], zq = pk.q_row >= 0 ? tot[1] : 1.0;
     const double inv_t = 1.0 / (double)pk.temperature, inv_zp = 1.0 / zp, inv_zq = 1.0 / zq;
     if (pk.q_row < 0) {
         if (own) sc[tid] = zp0 / zp;
         for (int c = tid + kThreads; c < w.nsub; c += kThreads) sc[c] = w.zp[ob + c] / zp;
-    } else if (namb <= kAmbCap) {
+    } else if (listed) {
         if (own) {
             const double m = pp0 * inv_zp - qq0 * inv_zq;
             sc[tid] = m > 0.0 ? m : 0.0;
@@ -574,33 +618,26 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
             sc[c] = m > 0.0 ? m : 0.0;
         }
         if (namb > 0) {
-            // The listed boundary entries, now that Zp and Zq are exact.  They arrive in no particular
-            // order: rank them by vocabulary id so that every block's additions happen in a fixed order.
-            __shared__ int amb_id[kAmbCap], amb_blk[kAmbCap];
-            __shared__ double amb_r[kAmbCap];
-            for (int e = tid; e < namb; e += kThreads) amb_id[e] = w.amb_idx[(int64_t)b * kAmbCap + e];
+            // The listed boundary entries, now that Zp and Zq are exact: lane c adds block c's run in its stored order.
             __syncthreads();
-            for (int e = tid; e < namb; e += kThreads) {
-                const int64_t l = (int64_t)b * kAmbCap + e;
-                const int id = amb_id[e];
-                int rank = 0;
-                for (int f = 0; f < namb; ++f) rank += amb_id[f] < id;
-                const double r = w.amb_ep[l] * inv_zp - w.amb_eq[l] * inv_zq;
-                amb_blk[rank] = id / kSub;
-                amb_r[rank] = r > 0.0 ? r : 0.0;
-            }
-            __syncthreads();
-            for (int e = tid; e < namb; e += kThreads) {
-                if (e == 0 || amb_blk[e - 1] != amb_blk[e]) {   // first listed entry of its block: add the block's run
+            for (int c = tid; c < w.nsub; c += kThreads) {
+                const int cnt = w.blk_cnt[ob + c];
+                if (cnt > 0) {
+                    const int64_t l0 = (int64_t)b * kAmbCap + w.blk_base[ob + c];
                     double add = 0.0;
-                    for (int f = e; f < namb && amb_blk[f] == amb_blk[e]; ++f) add += amb_r[f];
-                    sc[amb_blk[e]] += add;
+                    for (int e = 0; e < cnt; ++e) {
+                        const double r = w.amb_ep[l0 + e] * inv_zp - w.amb_eq[l0 + e] * inv_zq;
+                        add += r > 0.0 ? r : 0.0;
+                    }
+                    sc[c] += add;
                 }
             }
         }
     } else {
-        // Too many entries near p == q to list (rows that nearly coincide): every block's mass entry by entry.
-        for (int c = 0; c < w.nsub; ++c) {
+        // Too many entries near p == q to list (rows that nearly coincide, or many equal logit pairs on
+        // the boundary): the request's workgroups share the blocks and compute every mass entry by
+        // entry; the last one to deliver (a counter in device memory) goes on to draw the token.
+        for (int c = part; c < w.nsub; c += kPickWgs) {
             float yp[kSubPer], yq[kSubPer];
             load_slots<DT, kSubPer, false>(row_ptr(a.target, pk.p_row, a.row_stride, DT), a.vocab, c * kSub, tid, yp);
             load_slots<DT, kSubPer, false>(row_ptr(a.draft, pk.q_row, a.row_stride, DT), a.vocab, c * kSub, tid, yq);
@@ -610,6 +647,13 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
             m = block_sum<double>(m, wave_tot);
             if (tid == 0) sc[c] = m;
         }
+        __shared__ int ticket_sh;
+        __threadfence();   // the masses are out before the counter moves
+        __syncthreads();
+        if (tid == 0) ticket_sh = atomicAdd(&w.done[b], 1);
+        __syncthreads();
+        if (ticket_sh != kPickWgs - 1) return;
+        __threadfence();   // and the other workgroups' masses are read from memory, not from a stale cache line
     }
     __threadfence_block();
     __syncthreads();
@@ -745,8 +789,8 @@ size_t accept_workspace_bytes(int batch, int total_rows, int vocab)
     n += align_up(sizeof(RowPick) * (size_t)batch, 256);
     n += 5 * align_up(sizeof(double) * (size_t)batch * nsub, 256);
     n += 2 * align_up(sizeof(double) * (size_t)batch * kAmbCap, 256);
-    n += align_up(sizeof(int32_t) * (size_t)batch * kAmbCap, 256);
-    n += align_up(sizeof(int32_t) * (size_t)batch, 256);
+    n += 2 * align_up(sizeof(int32_t) * (size_t)batch * nsub, 256);
+    n += 2 * align_up(sizeof(int32_t) * (size_t)batch, 256);
     return n + 256;
 }
 
@@ -760,7 +804,7 @@ static int32_t accept_launch_dt(const AcceptArgs &a, const Workspace &w, unsigne
     if (a.greedy) return SS_OK;
     hipLaunchKernelGGL(accept_norm_kernel<DT>, dim3(g2), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_norm_kernel");
-    hipLaunchKernelGGL(accept_pick_kernel<DT>, dim3(a.batch), dim3(kThreads), 0, stream, a, w);
+    hipLaunchKernelGGL(accept_pick_kernel<DT>, dim3((unsigned)a.batch * kPickWgs), dim3(kThreads), 0, stream, a, w);
     SS_HIP_CHECK(hipGetLastError(), "launch accept_pick_kernel");
     return SS_OK;
 }
