@@ -247,6 +247,10 @@ int32_t ss_route_select(const ss_worker_metrics *workers, int32_t n, const doubl
  * Options (process-wide, not thread-safe; meant for tests and measurement).
  *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
  *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic
+ *   "validate"      1 = before launching, ss_spec_verify_attn, ss_kv_append and ss_spec_accept check the
+ *                   device-resident metadata with a small kernel (row offsets, lengths against block counts,
+ *                   block ids, draft tokens, temperatures, uniforms), synchronise the stream and return
+ *                   SS_ERR_INVALID_ARG naming the first inconsistency; 0 (default) = contents are trusted
  * Returns SS_ERR_INVALID_ARG for an unknown name or value.
  */
 int32_t ss_set_option(const char *name, int64_t value);

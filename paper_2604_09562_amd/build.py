@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["api.hip", "attn_mfma.hip", "attn_generic.hip", "accept.hip", "kvcache.hip", "depth_controller.cpp", "router.cpp"]
+SOURCES = ["api.hip", "attn_mfma.hip", "attn_generic.hip", "accept.hip", "kvcache.hip", "validate.hip", "depth_controller.cpp", "router.cpp"]
 
 
 def build(verbose: bool = False) -> str:

@@ -21,7 +21,6 @@ namespace ss {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kPerThread = kChunk / kThreads;  // 32 logits per lane in pass 1
 constexpr int kSub = 2048;                     // vocabulary entries per workgroup in the fp64 passes
 constexpr int kSubPer = kSub / kThreads;       // 8 logits per lane there
 constexpr int kMaxRows = 2 * SS_MAX_DEPTH + 1; // rows of one request: k+1 target, k draft

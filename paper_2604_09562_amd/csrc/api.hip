@@ -28,6 +28,7 @@ int32_t hip_fail(hipError_t e, const char *what)
 // process-wide options and profiling state
 static int64_t g_attn_path = 0;
 static int64_t g_attn_waves = 0;
+static int64_t g_validate = 0;
 static std::vector<hipEvent_t> g_events;  // pairs
 static int g_prof_cap = 0, g_prof_used = 0;
 
@@ -99,6 +100,11 @@ int32_t ss_set_option(const char *name, int64_t value)
         g_attn_waves = value;
         return SS_OK;
     }
+    if (!strcmp(name, "validate")) {
+        if (value < 0 || value > 1) return fail(SS_ERR_INVALID_ARG, "validate must be 0 or 1");
+        g_validate = value;
+        return SS_OK;
+    }
     return fail(SS_ERR_INVALID_ARG, "unknown option '%s'", name);
 }
 
@@ -132,6 +138,11 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
         return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (g_validate) {
+        rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch, batch->max_blocks_per_seq,
+                            kv->num_blocks, total_rows, static_cast<hipStream_t>(stream), "ss_spec_verify_attn");
+        if (rc != SS_OK) return rc;
+    }
 
     AttnArgs a{};
     a.k = kv->k; a.v = kv->v; a.k_scale = kv->k_scale; a.v_scale = kv->v_scale;
@@ -213,6 +224,14 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
         return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (g_validate) {
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, batch, 0, 0, total_rows, static_cast<hipStream_t>(stream),
+                                    "ss_spec_accept");
+        if (rc == SS_OK)
+            rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
+                                 static_cast<hipStream_t>(stream), "ss_spec_accept");
+        if (rc != SS_OK) return rc;
+    }
     AcceptArgs a{};
     a.batch = batch; a.vocab = vocab; a.logit_dtype = logit_dtype; a.total_rows = total_rows; a.greedy = greedy ? 1 : 0;
     a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft = draft_logits;
@@ -244,6 +263,12 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
         return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
     if ((kv->dtype == SS_FP8_E4M3) != (kv->k_scale != nullptr) || (kv->k_scale != nullptr) != (kv->v_scale != nullptr))
         return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
+    if (g_validate) {
+        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows,
+                                          static_cast<hipStream_t>(stream), "ss_kv_append");
+        if (rc != SS_OK) return rc;
+    }
     KvAppendArgs a{};
     a.k = const_cast<void *>(kv->k); a.v = const_cast<void *>(kv->v);
     a.k_scale = const_cast<float *>(kv->k_scale); a.v_scale = const_cast<float *>(kv->v_scale);
