@@ -199,8 +199,7 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 // OCC   wavefronts per SIMD the register budget is sized for
 // QLDS  keep the query operands in LDS (in operand order, one 1 KB line per row block and k-step)
 //       instead of registers: for many row blocks the registers are needed for the accumulators
-// SPLIT row blocks from SPLIT on are skipped for units with fewer rows (== NB: nothing is skipped)
-template <int G, int NB, bool FP8, int NBUF, int OCC, bool QLDS, int SPLIT>
+template <int G, int NB, bool FP8, int NBUF, int OCC, bool QLDS>
 __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
     const int32_t *__restrict__ tile_prefix,
@@ -239,7 +238,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
     // ---- state of the unit being computed ----
     int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
     int seg_left = 0;                 // of those, tiles that still belong to the current unit
-    int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has
+    int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has (for its partial)
     bf16x8 qreg[QLDS ? 1 : NB][4];    // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
     int lim[NB];                      // last visible cache position of this lane's row in block nb
     float m_run[NB], l_run[NB];
@@ -462,13 +461,9 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
         }
-        // Row blocks [0, SPLIT) are always computed (blocks beyond the unit's rows hold zero queries:
-        // cheaper than branching, never stored); the rest only for units that have that many rows.
-        rows_range(std::integral_constant<int, 0>{}, std::integral_constant<int, SPLIT>{}, t, vop, kop, tok0);
-        if constexpr (SPLIT < NB) {
-            if (nbu > SPLIT)
-                rows_range(std::integral_constant<int, SPLIT>{}, std::integral_constant<int, NB>{}, t, vop, kop, tok0);
-        }
+        // Row blocks beyond the unit's rows hold zero queries: they are computed anyway (cheaper than
+        // branching, which was measured) and never stored.
+        rows_range(std::integral_constant<int, 0>{}, std::integral_constant<int, NB>{}, t, vop, kop, tok0);
     };
 
     // one step of the compute side: consume a tile; at the end of a unit segment write its partial
@@ -600,7 +595,6 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     // pipeline fairly under saturation (the older one wins), which turns into a long tail.
     constexpr int OCC = 1;
     constexpr bool QLDS = NB >= 4;
-    constexpr int SPLIT = NB == 5 ? 3 : NB == 4 ? 2 : NB;
     constexpr int NBUF = NB <= 3 ? 4 : (NB == 5 && !FP8) ? 2 : 3;
     AttnArgs b = a;
     b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
@@ -610,7 +604,7 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     // When a profile is being taken the two events are attached to the dispatch itself, so that
     // their difference is the kernel's own duration on this stream (what a kernel trace shows).
-    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC, QLDS, SPLIT>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
+    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC, QLDS>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
                           dim3(64 * kWavesPerWg), 0, stream, ev0, ev1, 0, b, b.tile_addr, b.wave_desc, b.tile_prefix,
                           b.kv_len, b.q_indptr, b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
