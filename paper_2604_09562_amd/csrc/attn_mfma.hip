@@ -338,91 +338,54 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
         }
     };
 
-    // Row blocks [LO, HI) against one tile: S^T = K Q^T, softmax, O^T += V^T P^T.  Straight-line
-    // code apart from the rare rescale: masks are selects that are all-pass on ordinary tiles.
-    // (No branch may sit between an MFMA and the first read of its result: the wait states the
-    // hardware needs there are only inserted inside a block.)
-    auto rows_range = [&](auto lo_c, auto hi_c, const TileRegs<FP8> &t, const short4v (&vop)[8], const bf16x8 (&kop)[4],
-                          int tok0) {
-        constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
-        float4v s[HI - LO];
+    // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond the
+    // unit's rows hold zero queries; they are computed anyway (cheaper than branching, which was
+    // measured) and never stored.  Straight-line code apart from the rare rescale: masks are selects
+    // that are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
+    // its result: the wait states the hardware needs there are only inserted inside a block.)
+    // The order of the pieces is chosen so that vector work that does not depend on a matrix result
+    // follows each group of MFMAs: the V operands are built while S^T is in the matrix pipeline, and
+    // a row block's exponentials while the previous block's output MFMAs run.
+    auto compute = [&](const TileRegs<FP8> &t, int ti) {
+        const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
+
+        bf16x8 kop[4];
+        if constexpr (FP8) {
+            kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
+            kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
+            kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
+            kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
+        } else {
 #pragma unroll
-        for (int nb = LO; nb < HI; ++nb) s[nb - LO] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
+        }
+        float4v s[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
         if constexpr (QLDS) {
             // operands come from LDS a few MFMAs ahead of their use, so that its latency is covered
-            constexpr int NOPS = 4 * (HI - LO), AHEAD = NOPS < 6 ? NOPS : 6;
+            constexpr int NOPS = 4 * NB, AHEAD = NOPS < 6 ? NOPS : 6;
             uint4 qb[AHEAD];
 #pragma unroll
-            for (int i = 0; i < AHEAD; ++i) qb[i] = qs[((LO + i % (HI - LO)) * 4 + i / (HI - LO)) * 64];
+            for (int i = 0; i < AHEAD; ++i) qb[i] = qs[((i % NB) * 4 + i / NB) * 64];
 #pragma unroll
             for (int i = 0; i < NOPS; ++i) {
-                const int ks = i / (HI - LO), nb = LO + i % (HI - LO);
+                const int ks = i / NB, nb = i % NB;
                 const bf16x8 qop = __builtin_bit_cast(bf16x8, qb[i % AHEAD]);
                 if (i + AHEAD < NOPS) {
                     const int i2 = i + AHEAD;
-                    qb[i % AHEAD] = qs[((LO + i2 % (HI - LO)) * 4 + i2 / (HI - LO)) * 64];
+                    qb[i % AHEAD] = qs[((i2 % NB) * 4 + i2 / NB) * 64];
                 }
-                s[nb - LO] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qop, s[nb - LO], 0, 0, 0);
+                s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qop, s[nb], 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                for (int nb = LO; nb < HI; ++nb)
-                    s[nb - LO] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb - LO], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb)
+                    s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
         }
 
-        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
-        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
-        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
-        const float kscale = sc2 * t.ks;
-        float sv[HI - LO][4];
-        bool trig = false;
-#pragma unroll
-        for (int nb = LO; nb < HI; ++nb) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                sv[nb - LO][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb - LO][e] * kscale;
-            const float lane_mx = fmaxf(fmaxf(sv[nb - LO][0], sv[nb - LO][1]), fmaxf(sv[nb - LO][2], sv[nb - LO][3]));
-            trig |= lane_mx > m_run[nb] + kSlack;
-        }
-        if (__any(trig)) {
-#pragma unroll
-            for (int nb = LO; nb < HI; ++nb) {
-                float mx = fmaxf(fmaxf(sv[nb - LO][0], sv[nb - LO][1]), fmaxf(sv[nb - LO][2], sv[nb - LO][3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[nb], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-                l_run[nb] *= alpha;
-#pragma unroll
-                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
-                m_run[nb] = m_new;
-            }
-        }
-        short4v pop[HI - LO];
-#pragma unroll
-        for (int nb = LO; nb < HI; ++nb) {
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb - LO][e] - m_run[nb]);
-            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
-            uint2 pk;
-            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-            pop[nb - LO] = __builtin_bit_cast(short4v, pk);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb)
-#pragma unroll
-            for (int nb = LO; nb < HI; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop[nb - LO], acc[mb][nb], 0, 0, 0);
-    };
-
-    // One tile: operand registers of K and V, then the row blocks.
-    auto compute = [&](const TileRegs<FP8> &t, int ti) {
-        const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
         // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
         // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
         const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
@@ -451,19 +414,49 @@ __global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
             vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
         }
 
-        bf16x8 kop[4];
-        if constexpr (FP8) {
-            kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
-            kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
-            kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
-            kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
-        } else {
+        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
+        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
+        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
+        const float kscale = sc2 * t.ks;
+        float sv[NB][4];
+        bool trig = false;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+            const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+            trig |= lane_mx > m_run[nb] + kSlack;
         }
-        // Row blocks beyond the unit's rows hold zero queries: they are computed anyway (cheaper than
-        // branching, which was measured) and never stored.
-        rows_range(std::integral_constant<int, 0>{}, std::integral_constant<int, NB>{}, t, vop, kop, tok0);
+        if (__any(trig)) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[nb], mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+                l_run[nb] *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
+                m_run[nb] = m_new;
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float p[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
+            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+            uint2 pk;
+            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            const short4v pop = __builtin_bit_cast(short4v, pk);
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
+        }
     };
 
     // one step of the compute side: consume a tile; at the end of a unit segment write its partial
