@@ -73,7 +73,7 @@ int attn_default_waves()
     } else {
         (void)hipGetLastError();
     }
-    return cus * 8;  // two 4-wave workgroups per compute unit
+    return cus * 4;  // one wavefront per SIMD
 }
 
 }  // namespace ss

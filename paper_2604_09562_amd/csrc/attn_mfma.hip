@@ -196,11 +196,10 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 
 // NB    16-row blocks of query rows the kernel is compiled for (covers max_q_len * G rows)
 // NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
-// OCC   wavefronts per SIMD the register budget is sized for
 // QLDS  keep the query operands in LDS (in operand order, one 1 KB line per row block and k-step)
 //       instead of registers: for many row blocks the registers are needed for the accumulators
-template <int G, int NB, bool FP8, int NBUF, int OCC, bool QLDS>
-__global__ __launch_bounds__(64 * kWavesPerWg, OCC) void attn_stream_kernel(
+template <int G, int NB, bool FP8, int NBUF, bool QLDS>
+__global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
     const int32_t *__restrict__ tile_prefix,
     const int32_t *__restrict__ kv_len, const int32_t *__restrict__ q_indptr, const float *__restrict__ k_scale,
@@ -584,20 +583,17 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
 template <int G, int NB, bool FP8>
 int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
-    // One wave per SIMD with three tiles in flight: two waves on a SIMD do not share the memory
-    // pipeline fairly under saturation (the older one wins), which turns into a long tail.
-    constexpr int OCC = 1;
+    // One wavefront per SIMD (the whole register file, a ring of NBUF tiles): two waves on a SIMD
+    // do not share the memory pipeline fairly under saturation (the older one wins), which turns
+    // into a long tail.
     constexpr bool QLDS = NB >= 4;
     constexpr int NBUF = NB <= 3 ? 4 : (NB == 5 && !FP8) ? 2 : 3;
-    AttnArgs b = a;
-    b.launch_waves = a.launch_waves / 2 * OCC;   // a.launch_waves counts two waves per SIMD
-    b.launch_waves -= b.launch_waves % kWavesPerWg;
-    if (b.launch_waves < kWavesPerWg) b.launch_waves = kWavesPerWg;
+    const AttnArgs &b = a;
     hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     // When a profile is being taken the two events are attached to the dispatch itself, so that
     // their difference is the kernel's own duration on this stream (what a kernel trace shows).
-    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, OCC, QLDS>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
+    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, QLDS>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
                           dim3(64 * kWavesPerWg), 0, stream, ev0, ev1, 0, b, b.tile_addr, b.wave_desc, b.tile_prefix,
                           b.kv_len, b.q_indptr, b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
