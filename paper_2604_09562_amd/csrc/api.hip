@@ -140,7 +140,8 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
         rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch, batch->max_blocks_per_seq,
-                            kv->num_blocks, total_rows, static_cast<hipStream_t>(stream), "ss_spec_verify_attn");
+                            kv->num_blocks, total_rows, batch->max_q_len, static_cast<hipStream_t>(stream),
+                            "ss_spec_verify_attn");
         if (rc != SS_OK) return rc;
     }
 
@@ -225,7 +226,7 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
-        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, batch, 0, 0, total_rows, static_cast<hipStream_t>(stream),
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, batch, 0, 0, total_rows, 0, static_cast<hipStream_t>(stream),
                                     "ss_spec_accept");
         if (rc == SS_OK)
             rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
@@ -265,7 +266,7 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
         return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
     if (g_validate) {
         const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch,
-                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
                                           static_cast<hipStream_t>(stream), "ss_kv_append");
         if (rc != SS_OK) return rc;
     }

@@ -19,7 +19,7 @@ enum { CK_QLEN = 1, CK_QSTART, CK_QTOTAL, CK_KVLEN, CK_BLOCKS, CK_BLOCK_ID, CK_T
 
 __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *block_table, const int32_t *kv_len,
                                                              const int32_t *q_indptr, int batch, int max_blocks,
-                                                             int num_blocks, int total_rows, CheckRecord *out)
+                                                             int num_blocks, int total_rows, int max_q_len, CheckRecord *out)
 {
     __shared__ int bad_req;     // lowest request index with a problem
     const int tid = threadIdx.x;
@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *bloc
     // pass 1: find the first bad request (any kind of problem)
     for (int b = 0; b < batch; ++b) {
         const int q0 = q_indptr[b], q1 = q_indptr[b + 1], q_len = q1 - q0;
-        bool bad = q_len < 1 || q_len > SS_OUT_WIDTH || (b == 0 && q0 != 0) || (b == batch - 1 && q1 != total_rows);
+        bool bad = q_len < 1 || q_len > max_q_len || (b == 0 && q0 != 0) || (b == batch - 1 && q1 != total_rows);
         if (block_table) {
             const int L = kv_len[b];
             const long long nblk = ((long long)L + kTile - 1) / kTile;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *bloc
         const int q0 = q_indptr[b], q1 = q_indptr[b + 1], q_len = q1 - q0;
         r.where = b;
         if (b == 0 && q0 != 0) { r.code = CK_QSTART; r.value = q0; }
-        else if (q_len < 1 || q_len > SS_OUT_WIDTH) { r.code = CK_QLEN; r.value = q_len; }
+        else if (q_len < 1 || q_len > max_q_len) { r.code = CK_QLEN; r.value = q_len; r.aux = max_q_len; }
         else if (b == batch - 1 && q1 != total_rows) { r.code = CK_QTOTAL; r.value = q1; }
         else if (block_table) {
             const int L = kv_len[b];
@@ -116,7 +116,7 @@ int32_t report(const CheckRecord &r, const char *what)
 {
     switch (r.code) {
     case 0: return SS_OK;
-    case CK_QLEN: return fail(SS_ERR_INVALID_ARG, "%s: request %d has %d query rows (must be 1..%d)", what, r.where, r.value, SS_OUT_WIDTH);
+    case CK_QLEN: return fail(SS_ERR_INVALID_ARG, "%s: request %d has %d query rows (must be 1..%d)", what, r.where, r.value, r.aux);
     case CK_QSTART: return fail(SS_ERR_INVALID_ARG, "%s: q_indptr[0] is %d, not 0", what, r.value);
     case CK_QTOTAL: return fail(SS_ERR_INVALID_ARG, "%s: q_indptr[batch] is %d, not total_rows", what, r.value);
     case CK_KVLEN: return fail(SS_ERR_INVALID_ARG, "%s: request %d has kv_len %d but %d query rows", what, r.where, r.value, r.aux);
@@ -131,13 +131,13 @@ int32_t report(const CheckRecord &r, const char *what)
 }  // namespace
 
 int32_t validate_batch(const int32_t *block_table, const int32_t *kv_len, const int32_t *q_indptr, int batch,
-                       int max_blocks, int num_blocks, int total_rows, hipStream_t stream, const char *what)
+                       int max_blocks, int num_blocks, int total_rows, int max_q_len, hipStream_t stream, const char *what)
 {
     CheckRecord *host = nullptr, *dev = nullptr;
     const int32_t rc = record(&host, &dev);
     if (rc != SS_OK) return rc;
     hipLaunchKernelGGL(validate_batch_kernel, dim3(1), dim3(256), 0, stream, block_table, kv_len, q_indptr, batch, max_blocks,
-                       num_blocks, total_rows, dev);
+                       num_blocks, total_rows, max_q_len > 0 ? max_q_len : SS_OUT_WIDTH, dev);
     SS_HIP_CHECK(hipGetLastError(), "launch validate_batch_kernel");
     SS_HIP_CHECK(hipStreamSynchronize(stream), "hipStreamSynchronize (validation)");
     return report(*host, what);

@@ -83,6 +83,16 @@ def test_bad_attention_metadata_is_reported(validating, what):
         binding.ss_kv_append(binding.append_to_device(inp))
 
 
+def test_row_bound_hint_smaller_than_the_batch_needs(validating):
+    inp = attn_case()
+    d = binding.append_to_device(inp)
+    mq = int(inp["depth"].max())          # one less than the longest request has rows
+    out, lse, ws = binding.alloc_attention_outputs(d, max_q_len=mq)
+    with pytest.raises(binding.SpecVerifyError) as e:
+        binding.ss_spec_verify_attn(d, out, lse, ws, max_q_len=mq)
+    assert "query rows" in str(e.value)
+
+
 @pytest.mark.parametrize("what", ["token", "temperature", "uniform"])
 def test_bad_accept_inputs_are_reported(validating, what):
     acc = synth.make_accept_inputs(LLAMA8B.scaled(batch=6, vocab=5000), seed=2)
