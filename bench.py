@@ -76,6 +76,8 @@ def main() -> int:
                     help="after timing, launch a plain device copy of this size three times: the known-size "
                          "kernel that scales FETCH_SIZE / WRITE_SIZE in a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
+    ap.add_argument("--tree", action="store_true",
+                    help="the drafts of every request form a random tree instead of a chain (same shapes and sizes)")
     ap.add_argument("--attn-waves", type=int, default=0, help="KV partitions of the attention kernel (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,7 +100,7 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    att = synth.make_attention_inputs(cfg, seed=args.seed)
+    att = synth.make_attention_inputs(cfg, seed=args.seed, tree=args.tree)
     acc = synth.make_accept_inputs(cfg, seed=args.seed, depth=att["depth"])
     max_q_len = int(att["depth"].max()) + 1
     kv_bytes = synth.kv_bytes_algorithmic(att)
@@ -164,7 +166,8 @@ def main() -> int:
         "config": {"workload": cfg.name, "batch": att["batch"], "num_q_heads": cfg.num_q_heads,
                    "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "query_tokens": q_tokens,
                    "kv_tokens": int(att["kv_len"].astype(np.int64).sum()), "vocab": cfg.vocab,
-                   "max_q_len": max_q_len, "rotated_copies": nrot, "seed": args.seed},
+                   "max_q_len": max_q_len, "rotated_copies": nrot, "seed": args.seed,
+                   "drafts": "tree" if args.tree else "chain"},
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg.name),
                      "algorithmic_bytes": kv_bytes, "kernel_ms_avg": kern_avg_ms,

@@ -89,6 +89,13 @@ typedef struct ss_paged_kv {
  *                this step, plus one), or 0 if unknown (9 is assumed).  A tight bound lets the
  *                library pick a kernel with fewer padded query rows; a bound that some request
  *                exceeds is a caller error (rows beyond it are not computed).
+ *   tree_mask    NULL: the new tokens of a request form a chain (row i attends new tokens 0..i).
+ *                Otherwise device uint32 [total rows]: the new tokens form a draft tree (tree-structured
+ *                drafts as in the EAGLE family the paper's Section 5.1 uses as its draft model) with row 0
+ *                the root; bit j of a row's word says that the row attends new token j of its own request
+ *                (position kv_len-q_len+j), i.e. that node j is the row's own node or an ancestor of it.
+ *                Every row's own bit must be set and no bit at or above q_len; the context before the new
+ *                tokens is always visible.  Read by ss_spec_verify_attn only.
  */
 typedef struct ss_batch {
     int32_t batch;
@@ -98,6 +105,7 @@ typedef struct ss_batch {
     const int32_t *block_table;
     const int32_t *kv_len;
     const int32_t *q_indptr;
+    const uint32_t *tree_mask;
 } ss_batch;
 
 /* Library version (major*10000 + minor*100 + patch). */

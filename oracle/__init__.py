@@ -70,7 +70,8 @@ def verify_attn(inp: Dict[str, object], *, part_tokens: int = 0,
     """Run the attention oracle on a batch dict from ``synth.make_attention_inputs``.
 
     Returns (out[R,Hq,D] float64, lse[R,Hq] float64); rows of requests not in
-    ``requests`` are NaN.
+    ``requests`` are NaN.  A ``tree_mask`` entry in the dict (uint32 per query row) makes the new
+    tokens a draft tree; without it they are a chain.
     """
     lib = _load()
     R, Hq, D = inp["total_rows"], inp["num_q_heads"], inp["head_dim"]
@@ -82,7 +83,7 @@ def verify_attn(inp: Dict[str, object], *, part_tokens: int = 0,
         ctypes.c_int(D), ctypes.c_int(inp["block_size"]), ctypes.c_int(inp["max_blocks_per_seq"]),
         ctypes.c_int(_DT[inp["kv_dtype"]]), _p(inp["k_cache"]), _p(inp["v_cache"]),
         _p(inp["k_scale"]), _p(inp["v_scale"]), _p(inp["block_table"]), _p(inp["kv_len"]),
-        _p(inp["q_indptr"]), ctypes.c_int(_DT[inp["q_dtype"]]), _p(inp["q"]),
+        _p(inp["q_indptr"]), _p(inp.get("tree_mask")), ctypes.c_int(_DT[inp["q_dtype"]]), _p(inp["q"]),
         ctypes.c_double(inp["sm_scale"]), ctypes.c_int(part_tokens), _p(req),
         ctypes.c_int(0 if req is None else len(req)), _p(out), _p(lse), ctypes.c_int(threads))
     if rc != 0:

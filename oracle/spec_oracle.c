@@ -88,6 +88,12 @@ void oracle_decode(const void *src, int64_t n, int dtype, double *dst)
  * cache positions 0..pos_i (causal among the new tokens, everything older is
  * visible).  Query head h reads KV head h / (Hq/Hkv).
  *
+ * With tree_mask != NULL the new tokens form a draft tree instead of a chain
+ * (node 0 is the last accepted token, node j's parent has a smaller index): bit
+ * j of tree_mask[row] says that the row attends new token j, i.e. that j is the
+ * row's own node or one of its ancestors; the older context stays fully visible.
+ * The chain is the special case tree_mask[row i] = 2^(i+1) - 1.
+ *
  *     s_t = sm_scale * <Q[row,h,:], K[t,:]>        t = 0..pos_i
  *     out = sum_t softmax(s)_t * V[t,:]            lse = ln sum_t exp(s_t)
  *
@@ -107,13 +113,14 @@ void oracle_decode(const void *src, int64_t n, int dtype, double *dst)
  */
 static void attend_range(const double *qrow, int D, int dtype, const void *kc, const void *vc,
                          const float *k_scale, const float *v_scale, const int32_t *bt_row,
-                         int Hkv, int g, int bs, int t0, int t1, double sm_scale,
+                         int Hkv, int g, int bs, const int *pos, int t0, int t1, double sm_scale,
                          double *s /*scratch t1-t0*/, double *out /*D*/, double *lse)
 {
+    /* attends the cache positions pos[t0..t1) */
     double m = -INFINITY;
     for (int t = t0; t < t1; ++t) {
-        int64_t phys = bt_row[t / bs];
-        int64_t base = ((phys * Hkv + g) * bs + (t % bs)) * (int64_t)D;
+        int64_t phys = bt_row[pos[t] / bs];
+        int64_t base = ((phys * Hkv + g) * bs + (pos[t] % bs)) * (int64_t)D;
         double acc = 0.0;
         for (int d = 0; d < D; ++d)
             acc += qrow[d] * load_elem(kc, base + d, dtype);
@@ -131,8 +138,8 @@ static void attend_range(const double *qrow, int D, int dtype, const void *kc, c
     for (int d = 0; d < D; ++d)
         out[d] = 0.0;
     for (int t = t0; t < t1; ++t) {
-        int64_t phys = bt_row[t / bs];
-        int64_t base = ((phys * Hkv + g) * bs + (t % bs)) * (int64_t)D;
+        int64_t phys = bt_row[pos[t] / bs];
+        int64_t base = ((phys * Hkv + g) * bs + (pos[t] % bs)) * (int64_t)D;
         double w = s[t - t0] / l;
         if (v_scale)
             w *= (double)v_scale[phys * Hkv + g];
@@ -145,8 +152,8 @@ static void attend_range(const double *qrow, int D, int dtype, const void *kc, c
 int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, int kv_dtype,
                        const void *k_cache, const void *v_cache, const float *k_scale,
                        const float *v_scale, const int32_t *block_table, const int32_t *kv_len,
-                       const int32_t *q_indptr, int q_dtype, const void *q, double sm_scale,
-                       int part_tokens, const int32_t *req_list, int n_req, double *out,
+                       const int32_t *q_indptr, const uint32_t *tree_mask, int q_dtype, const void *q,
+                       double sm_scale, int part_tokens, const int32_t *req_list, int n_req, double *out,
                        double *lse, int num_threads)
 {
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || D <= 0 || bs <= 0 || part_tokens < 0)
@@ -159,6 +166,12 @@ int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, in
         int ql = q_indptr[b + 1] - q_indptr[b];
         if (ql < 1 || kv_len[b] < ql || (kv_len[b] + bs - 1) / bs > max_blocks)
             return -4;
+        /* a row of a draft tree sees itself and only new tokens of its own request */
+        for (int i = 0; tree_mask && i < ql; ++i) {
+            uint32_t mk = tree_mask[q_indptr[b] + i];
+            if (ql > 32 || !((mk >> i) & 1u) || (ql < 32 && (mk >> ql)))
+                return -6;
+        }
     }
     int G = Hq / Hkv;
     int n = req_list ? n_req : B;
@@ -179,22 +192,32 @@ int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, in
             const int32_t *bt_row = block_table + (int64_t)b * max_blocks;
             double *s = (double *)malloc(sizeof(double) * (size_t)L);
             double *qrow = (double *)malloc(sizeof(double) * (size_t)D * 3);
-            if (!s || !qrow) {
+            int *pos = (int *)malloc(sizeof(int) * (size_t)L);
+            if (!s || !qrow || !pos) {
                 fail = 1;
                 free(s);
                 free(qrow);
+                free(pos);
                 continue;
             }
             double *o_part = qrow + D, *o_sum = qrow + 2 * D;
             for (int i = 0; i < ql; ++i) {
                 int64_t row = q_indptr[b] + i;
-                int vis = L - ql + i + 1; /* positions 0..pos_i */
+                /* Visible positions, ascending: the whole context before this step's tokens, then
+                 * new token j (at position L-ql+j) if it is an ancestor of row i or row i itself.
+                 * In a chain that is every j <= i; in a tree the mask's bit j says so. */
+                int vis = 0;
+                for (int t = 0; t < L; ++t) {
+                    int j = t - (L - ql);
+                    if (j < 0 || (tree_mask ? (int)((tree_mask[row] >> j) & 1u) : j <= i))
+                        pos[vis++] = t;
+                }
                 double *o = out + (row * Hq + h) * (int64_t)D;
                 for (int d = 0; d < D; ++d)
                     qrow[d] = load_elem(q, (row * Hq + h) * (int64_t)D + d, q_dtype);
                 if (part_tokens == 0) {
                     attend_range(qrow, D, kv_dtype, k_cache, v_cache, k_scale, v_scale, bt_row,
-                                 Hkv, g, bs, 0, vis, sm_scale, s, o, &lse[row * Hq + h]);
+                                 Hkv, g, bs, pos, 0, vis, sm_scale, s, o, &lse[row * Hq + h]);
                 } else {
                     /* split into pieces, then merge the pieces by their log-sum-exp */
                     int np = (vis + part_tokens - 1) / part_tokens;
@@ -205,7 +228,7 @@ int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, in
                         int t0 = p * part_tokens;
                         int t1 = t0 + part_tokens < vis ? t0 + part_tokens : vis;
                         attend_range(qrow, D, kv_dtype, k_cache, v_cache, k_scale, v_scale,
-                                     bt_row, Hkv, g, bs, t0, t1, sm_scale, s, o_part, &pl[p]);
+                                     bt_row, Hkv, g, bs, pos, t0, t1, sm_scale, s, o_part, &pl[p]);
                         memcpy(po + (size_t)p * D, o_part, sizeof(double) * D);
                         if (pl[p] > mx)
                             mx = pl[p];
@@ -228,6 +251,7 @@ int oracle_verify_attn(int B, int Hq, int Hkv, int D, int bs, int max_blocks, in
             }
             free(s);
             free(qrow);
+            free(pos);
         }
     }
     return fail ? -5 : 0;

@@ -40,7 +40,8 @@ class ss_paged_kv(ctypes.Structure):
 class ss_batch(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
                 ("max_q_len", ctypes.c_int32), ("reserved", ctypes.c_int32),
-                ("block_table", ctypes.c_void_p), ("kv_len", ctypes.c_void_p), ("q_indptr", ctypes.c_void_p)]
+                ("block_table", ctypes.c_void_p), ("kv_len", ctypes.c_void_p), ("q_indptr", ctypes.c_void_p),
+                ("tree_mask", ctypes.c_void_p)]
 
 
 SS_FLOW_MAX = 64
@@ -149,6 +150,8 @@ def _to_dev(a: Optional[np.ndarray], device) -> Optional[torch.Tensor]:
     a = np.ascontiguousarray(a)
     if a.dtype == np.uint16:  # bf16 bits
         return torch.from_numpy(a.view(np.int16)).to(device)
+    if a.dtype == np.uint32:  # bit masks
+        return torch.from_numpy(a.view(np.int32)).to(device)
     return torch.from_numpy(a).to(device)
 
 
@@ -157,6 +160,8 @@ def attention_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, ob
     d = dict(inp)
     for name in ("k_cache", "v_cache", "k_scale", "v_scale", "block_table", "kv_len", "q_indptr", "q"):
         d[name] = _to_dev(inp[name], device)
+    if inp.get("tree_mask") is not None:
+        d["tree_mask"] = _to_dev(inp["tree_mask"], device)
     return d
 
 
@@ -181,7 +186,8 @@ def _descriptors(d: Dict[str, object], max_q_len: int):
                      0 if d["k_scale"] is None else d["k_scale"].data_ptr(),
                      0 if d["v_scale"] is None else d["v_scale"].data_ptr())
     bt = ss_batch(d["batch"], d["max_blocks_per_seq"], max_q_len, 0, d["block_table"].data_ptr(),
-                  d["kv_len"].data_ptr(), d["q_indptr"].data_ptr())
+                  d["kv_len"].data_ptr(), d["q_indptr"].data_ptr(),
+                  d["tree_mask"].data_ptr() if d.get("tree_mask") is not None else 0)
     return kv, bt
 
 

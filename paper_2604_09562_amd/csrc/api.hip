@@ -139,7 +139,7 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
-        rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch, batch->max_blocks_per_seq,
+        rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->tree_mask, batch->batch, batch->max_blocks_per_seq,
                             kv->num_blocks, total_rows, batch->max_q_len, static_cast<hipStream_t>(stream),
                             "ss_spec_verify_attn");
         if (rc != SS_OK) return rc;
@@ -150,6 +150,7 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.num_kv_heads = kv->num_kv_heads; a.head_dim = kv->head_dim; a.kv_dtype = kv->dtype;
     a.batch = batch->batch; a.max_blocks = batch->max_blocks_per_seq;
     a.block_table = batch->block_table; a.kv_len = batch->kv_len; a.q_indptr = batch->q_indptr;
+    a.tree_mask = batch->tree_mask;
     a.q = q; a.out = out; a.lse = lse; a.q_dtype = q_dtype; a.num_q_heads = num_q_heads; a.total_rows = total_rows;
     a.sm_scale = sm_scale;
     a.launch_waves = launch_waves;
@@ -226,7 +227,7 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
-        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, batch, 0, 0, total_rows, 0, static_cast<hipStream_t>(stream),
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, 0, static_cast<hipStream_t>(stream),
                                     "ss_spec_accept");
         if (rc == SS_OK)
             rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
@@ -265,7 +266,7 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
     if ((kv->dtype == SS_FP8_E4M3) != (kv->k_scale != nullptr) || (kv->k_scale != nullptr) != (kv->v_scale != nullptr))
         return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
     if (g_validate) {
-        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, batch->batch,
+        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
                                           batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
                                           static_cast<hipStream_t>(stream), "ss_kv_append");
         if (rc != SS_OK) return rc;

@@ -39,7 +39,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnArgs a)
     }
     const int b = lo;
     const int q0 = a.q_indptr[b], q_len = a.q_indptr[b + 1] - q0;
-    const int visible = a.kv_len[b] - q_len + (row - q0) + 1;  // cache positions 0..visible-1
+    // Visible cache positions: everything before this step's new tokens, then the new tokens the
+    // row's mask word names (its own node and its ancestors); for a chain those are tokens 0..i.
+    const int ctx = a.kv_len[b] - q_len;
+    const uint32_t newmask = a.tree_mask ? a.tree_mask[row] : (2u << (row - q0)) - 1u;
+    const int visible = ctx + 32 - __builtin_clz(newmask | 1u);  // one past the last visible position
     const int64_t qoff = ((int64_t)row * a.num_q_heads + h) * D;
 
     for (int d = tid; d < D; d += 256) q_s[d] = load_as_float(a.q, qoff + d, a.q_dtype);
@@ -52,6 +56,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnArgs a)
 
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks;
     for (int t = tid; t < visible; t += 256) {
+        if (t >= ctx && !((newmask >> (t - ctx)) & 1u)) continue;
         const int64_t phys = bt[t / kTile];
         const int64_t base = ((phys * a.num_kv_heads + g) * kTile + (t % kTile)) * D;
         float s = 0.f;

@@ -198,7 +198,9 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
 // NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
 // QLDS  keep the query operands in LDS (in operand order, one 1 KB line per row block and k-step)
 //       instead of registers: for many row blocks the registers are needed for the accumulators
-template <int G, int NB, bool FP8, int NBUF, bool QLDS>
+// TREE  the new tokens of a request form a draft tree: a row's visibility among them comes from its
+//       mask word instead of the chain's "tokens up to my own"
+template <int G, int NB, bool FP8, int NBUF, bool QLDS, bool TREE>
 __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
     const int32_t *__restrict__ tile_prefix,
@@ -239,7 +241,9 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     int seg_left = 0;                 // of those, tiles that still belong to the current unit
     int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has (for its partial)
     bf16x8 qreg[QLDS ? 1 : NB][4];    // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
-    int lim[NB];                      // last visible cache position of this lane's row in block nb
+    int lim[TREE ? 1 : NB];           // chain: last visible cache position of this lane's row in block nb
+    uint32_t newmask[TREE ? NB : 1];  // tree: which new tokens of the request the lane's row attends
+    int ctx = 0;                      // cache positions before the unit's new tokens
     float m_run[NB], l_run[NB];
     float4v acc[8][NB];
     const float sc2 = a.sm_scale * kLog2e;
@@ -252,6 +256,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         nb_tiles = meta_nbt;
         rows = q_len * G;
         nbu = (rows + 15) >> 4;
+        ctx = L - q_len;
         {
             const int nb_ = (g + 1 == a.num_kv_heads) ? b + 1 : b;   // request of the next unit
             if (nb_ != b && nb_ < a.batch) {
@@ -267,7 +272,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             const int n = nb * 16 + r16;
             const bool ok = n < rows;
             const int qi = n / G, hh = n % G;
-            lim[nb] = ok ? L - q_len + qi : L - 1;
+            if constexpr (TREE)   // padding rows see every new token: harmless, and no row is empty
+                newmask[nb] = ok ? a.tree_mask[q0 + qi] : (2u << (q_len - 1)) - 1u;
+            else
+                lim[nb] = ok ? L - q_len + qi : L - 1;
             const char *qp = static_cast<const char *>(a.q) +
                              (((long long)(q0 + qi) * a.num_q_heads + g * G + hh) * D) * 2;
 #pragma unroll
@@ -294,6 +302,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
+        }
+        if constexpr (TREE) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(newmask[nb]));
         }
     };
 
@@ -421,9 +433,20 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         bool trig = false;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
+            if constexpr (TREE) {
+                // A 64-position window: 32 positions of old context (all visible) below the 32 mask
+                // bits of the new tokens; shifted so that bit e is this lane's position tok0 + e.
+                // Positions past the cache end are past the mask's last set bit.
+                const int sh = tok0 - ctx + 32;
+                const uint64_t window = ((uint64_t)newmask[nb] << 32) | 0xffffffffull;
+                const uint32_t vis = sh < 0 ? 0xfu : (uint32_t)(window >> (sh & 63));
 #pragma unroll
-            for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+                for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? s[nb][e] * kscale : -INFINITY;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                    sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+            }
             const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
             trig |= lane_mx > m_run[nb] + kSlack;
         }
@@ -580,7 +603,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     if (a.lse && d4 == 0) a.lse[orow] = (m_all + log2f(l_all)) * kLn2;
 }
 
-template <int G, int NB, bool FP8>
+template <int G, int NB, bool FP8, bool TREE>
 int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
     // One wavefront per SIMD (the whole register file, a ring of NBUF tiles): two waves on a SIMD
@@ -593,7 +616,7 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
     // When a profile is being taken the two events are attached to the dispatch itself, so that
     // their difference is the kernel's own duration on this stream (what a kernel trace shows).
-    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, QLDS>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
+    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, QLDS, TREE>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
                           dim3(64 * kWavesPerWg), 0, stream, ev0, ev1, 0, b, b.tile_addr, b.wave_desc, b.tile_prefix,
                           b.kv_len, b.q_indptr, b.k_scale, b.v_scale);
     SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
@@ -606,8 +629,12 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
 template <int G, int NB>
 int32_t launch_nb(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
-    if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true>(a, stream, ev0, ev1);
-    return launch_stream<G, NB, false>(a, stream, ev0, ev1);
+    if (a.tree_mask) {
+        if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true, true>(a, stream, ev0, ev1);
+        return launch_stream<G, NB, false, true>(a, stream, ev0, ev1);
+    }
+    if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true, false>(a, stream, ev0, ev1);
+    return launch_stream<G, NB, false, false>(a, stream, ev0, ev1);
 }
 
 template <int G>

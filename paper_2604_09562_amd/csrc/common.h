@@ -43,6 +43,7 @@ struct AttnArgs {
     // batch
     int32_t batch, max_blocks;
     const int32_t *block_table, *kv_len, *q_indptr;
+    const uint32_t *tree_mask;   // per query row, or nullptr for chains: which new tokens of its request the row attends
     // query / output
     const void *q;
     void *out;
@@ -100,8 +101,8 @@ int32_t kv_commit_launch(int batch, const int32_t *q_indptr, const int32_t *acce
                          hipStream_t stream);
 
 // ---- optional checks of device-resident metadata (option "validate") ---------------------------------
-int32_t validate_batch(const int32_t *block_table, const int32_t *kv_len, const int32_t *q_indptr, int batch,
-                       int max_blocks, int num_blocks, int total_rows, int max_q_len, hipStream_t stream, const char *what);
+int32_t validate_batch(const int32_t *block_table, const int32_t *kv_len, const int32_t *q_indptr,
+                       const uint32_t *tree_mask, int batch, int max_blocks, int num_blocks, int total_rows, int max_q_len, hipStream_t stream, const char *what);
 int32_t validate_accept(const int32_t *draft_tokens, const float *u_accept, const float *u_sample, const float *temperature,
                         int batch, int n_draft, int vocab, int greedy, hipStream_t stream, const char *what);
 

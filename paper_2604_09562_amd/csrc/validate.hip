@@ -15,11 +15,12 @@ struct CheckRecord {
     int32_t aux;
 };
 
-enum { CK_QLEN = 1, CK_QSTART, CK_QTOTAL, CK_KVLEN, CK_BLOCKS, CK_BLOCK_ID, CK_TOKEN, CK_TEMP, CK_UNIFORM };
+enum { CK_QLEN = 1, CK_QSTART, CK_QTOTAL, CK_KVLEN, CK_BLOCKS, CK_BLOCK_ID, CK_TOKEN, CK_TEMP, CK_UNIFORM, CK_TREE };
 
 __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *block_table, const int32_t *kv_len,
-                                                             const int32_t *q_indptr, int batch, int max_blocks,
-                                                             int num_blocks, int total_rows, int max_q_len, CheckRecord *out)
+                                                             const int32_t *q_indptr, const uint32_t *tree_mask, int batch,
+                                                             int max_blocks, int num_blocks, int total_rows, int max_q_len,
+                                                             CheckRecord *out)
 {
     __shared__ int bad_req;     // lowest request index with a problem
     const int tid = threadIdx.x;
@@ -38,6 +39,11 @@ __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *bloc
                 const int id = block_table[(long long)b * max_blocks + t];
                 if (id < 0 || id >= num_blocks) bad = true;
             }
+        }
+        // a tree row attends itself and only new tokens of its own request
+        if (tree_mask && q_len >= 1 && q_len <= max_q_len && q0 >= 0 && q1 <= total_rows && tid < q_len) {
+            const uint32_t w = tree_mask[q0 + tid];
+            if (!((w >> tid) & 1u) || (w >> q_len)) bad = true;
         }
         if (bad) atomicMin(&bad_req, b);
         __syncthreads();
@@ -63,6 +69,12 @@ __global__ __launch_bounds__(256) void validate_batch_kernel(const int32_t *bloc
                     const int id = block_table[(long long)b * max_blocks + t];
                     if (id < 0 || id >= num_blocks) { r.code = CK_BLOCK_ID; r.value = id; r.aux = t; break; }
                 }
+            }
+        }
+        if (r.code == 0 && tree_mask) {
+            for (int i = 0; i < q_len; ++i) {
+                const uint32_t w = tree_mask[q0 + i];
+                if (!((w >> i) & 1u) || (w >> q_len)) { r.code = CK_TREE; r.value = i; r.aux = (int32_t)w; break; }
             }
         }
     }
@@ -124,19 +136,20 @@ int32_t report(const CheckRecord &r, const char *what)
     case CK_BLOCK_ID: return fail(SS_ERR_INVALID_ARG, "%s: request %d, logical block %d maps to physical block %d (out of range)", what, r.where, r.aux, r.value);
     case CK_TOKEN: return fail(SS_ERR_INVALID_ARG, "%s: draft token %d at draft row %d is outside the vocabulary", what, r.value, r.where);
     case CK_TEMP: return fail(SS_ERR_INVALID_ARG, "%s: request %d has a non-positive temperature", what, r.where);
+    case CK_TREE: return fail(SS_ERR_INVALID_ARG, "%s: request %d, row %d has tree mask 0x%x (own bit missing or a bit past its query rows)", what, r.where, r.value, (unsigned)r.aux);
     default: return fail(SS_ERR_INVALID_ARG, "%s: uniform %d is outside [0, 1)", what, r.where);
     }
 }
 
 }  // namespace
 
-int32_t validate_batch(const int32_t *block_table, const int32_t *kv_len, const int32_t *q_indptr, int batch,
-                       int max_blocks, int num_blocks, int total_rows, int max_q_len, hipStream_t stream, const char *what)
+int32_t validate_batch(const int32_t *block_table, const int32_t *kv_len, const int32_t *q_indptr,
+                       const uint32_t *tree_mask, int batch, int max_blocks, int num_blocks, int total_rows, int max_q_len, hipStream_t stream, const char *what)
 {
     CheckRecord *host = nullptr, *dev = nullptr;
     const int32_t rc = record(&host, &dev);
     if (rc != SS_OK) return rc;
-    hipLaunchKernelGGL(validate_batch_kernel, dim3(1), dim3(256), 0, stream, block_table, kv_len, q_indptr, batch, max_blocks,
+    hipLaunchKernelGGL(validate_batch_kernel, dim3(1), dim3(256), 0, stream, block_table, kv_len, q_indptr, tree_mask, batch, max_blocks,
                        num_blocks, total_rows, max_q_len > 0 ? max_q_len : SS_OUT_WIDTH, dev);
     SS_HIP_CHECK(hipGetLastError(), "launch validate_batch_kernel");
     SS_HIP_CHECK(hipStreamSynchronize(stream), "hipStreamSynchronize (validation)");

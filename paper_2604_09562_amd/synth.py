@@ -144,13 +144,16 @@ def draw_lengths(cfg: VerifyConfig, seed: int) -> Tuple[np.ndarray, np.ndarray]:
 def make_attention_inputs(cfg: VerifyConfig, seed: int = 0, *,
                           nan_tail: bool = False,
                           kv_len: Optional[np.ndarray] = None,
-                          depth: Optional[np.ndarray] = None) -> Dict[str, object]:
+                          depth: Optional[np.ndarray] = None,
+                          tree: bool = False) -> Dict[str, object]:
     """Draw one batch for spec_verify_attn.
 
     Returns a dict of numpy arrays in storage format plus the scalar shape
     fields.  Slots past kv_len in a request's last block hold large finite
     garbage (NaN bytes when ``nan_tail``), pool blocks no request references
     hold NaN bytes, and block-table padding is -1: real caches look like that.
+    With ``tree`` the new tokens of every request form a random draft tree
+    (``tree_parent``, ``tree_mask``; see ``draw_draft_trees``) instead of a chain.
     """
     if kv_len is None or depth is None:
         kv_len_d, depth_d = draw_lengths(cfg, seed)
@@ -218,7 +221,7 @@ def make_attention_inputs(cfg: VerifyConfig, seed: int = 0, *,
             k_cache[last, :, r:, :] = tail_val
             v_cache[last, :, r:, :] = tail_val
 
-    return dict(
+    out = dict(
         batch=B, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, block_size=BLOCK_SIZE,
         num_blocks=num_blocks, max_blocks_per_seq=max_blocks, total_rows=R,
         kv_dtype=cfg.kv_dtype, q_dtype=cfg.q_dtype,
@@ -226,6 +229,31 @@ def make_attention_inputs(cfg: VerifyConfig, seed: int = 0, *,
         block_table=block_table, k_cache=k_cache, v_cache=v_cache,
         k_scale=k_scale, v_scale=v_scale, q=q, sm_scale=float(1.0 / math.sqrt(D)),
     )
+    if tree:
+        out["tree_parent"], out["tree_mask"] = draw_draft_trees(q_indptr, _rng(cfg, seed, 10))
+    return out
+
+
+def draw_draft_trees(q_indptr: np.ndarray, rng: np.random.Generator):
+    """Random draft trees over the query rows of a batch.
+
+    Row 0 of a request is the tree's root (the last accepted token); row i > 0 is a draft node whose
+    parent is drawn uniformly from rows 0..i-1 of the same request, so parents precede children, as
+    in a tree stored level by level or in depth-first order.  Returns ``tree_parent`` (int32 per
+    row, index within the request, -1 for the root) and ``tree_mask`` (uint32 per row: bit j set
+    iff row j of the request is the row itself or one of its ancestors).
+    """
+    R = int(q_indptr[-1])
+    parent = np.full(R, -1, dtype=np.int32)
+    mask = np.zeros(R, dtype=np.uint32)
+    for b in range(len(q_indptr) - 1):
+        r0, n = int(q_indptr[b]), int(q_indptr[b + 1] - q_indptr[b])
+        mask[r0] = 1
+        for i in range(1, n):
+            p = int(rng.integers(0, i))
+            parent[r0 + i] = p
+            mask[r0 + i] = mask[r0 + p] | np.uint32(1 << i)
+    return parent, mask
 
 
 def make_append_inputs(cfg: VerifyConfig, seed: int = 0, **kw) -> Dict[str, object]:

@@ -39,7 +39,14 @@ def _sdpa_reference(inp):
         Q = torch.from_numpy(q[r0:r1]).permute(1, 0, 2)  # [Hq, ql, D]
         mask = torch.zeros(ql, L, dtype=torch.bool)
         for i in range(ql):
-            mask[i, : L - ql + i + 1] = True
+            if "tree_parent" in inp:   # a tree row sees the old context, itself and its ancestors
+                mask[i, : L - ql] = True
+                j = i
+                while j >= 0:
+                    mask[i, L - ql + j] = True
+                    j = int(inp["tree_parent"][r0 + j])
+            else:
+                mask[i, : L - ql + i + 1] = True
         o = torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=mask, scale=inp["sm_scale"])
         out[r0:r1] = o.permute(1, 0, 2).numpy()
     return out
@@ -105,6 +112,63 @@ def test_hand_worked_example(oracle):
     w = np.exp([0.5, -1.0, -0.5])
     assert out[1, 0] == pytest.approx((w @ V.astype(np.float64)) / w.sum(), abs=1e-14)
     assert lse[1, 0] == pytest.approx(math.log(w.sum()), abs=1e-14)
+
+
+@pytest.mark.parametrize("kv_dtype,q_dtype", [("f32", "f32"), ("bf16", "bf16"), ("fp8", "bf16")])
+def test_draft_tree_matches_library_attention(oracle, kv_dtype, q_dtype):
+    # the library's mask is built here by walking parent pointers, not from the mask words the oracle reads
+    cfg = _small(kv_dtype, q_dtype, batch=6, ctx=("fixed", (1, 9, 16, 37, 64, 131)), depth=("uniform", 0, 8))
+    inp = synth.make_attention_inputs(cfg, seed=11, tree=True, kv_len=np.array([9, 9, 16, 37, 64, 131]),
+                                      depth=np.array([8, 0, 3, 8, 5, 8]))
+    par = inp["tree_parent"]
+    assert any(par[r] != r - inp["q_indptr"][b] - 1 for b in range(6)
+               for r in range(inp["q_indptr"][b] + 1, inp["q_indptr"][b + 1])), "the draw produced only chains"
+    out, lse = oracle.verify_attn(inp)
+    assert np.max(np.abs(out - _sdpa_reference(inp))) < 1e-11
+    o2, l2 = oracle.verify_attn(inp, part_tokens=16)
+    assert np.max(np.abs(o2 - out)) < 1e-12 and np.max(np.abs(l2 - lse)) < 1e-12
+
+
+def test_chain_written_as_a_tree_is_the_chain(oracle):
+    cfg = _small("bf16", "bf16", depth=("uniform", 0, 8), batch=5, ctx=("uniform", 20, 150))
+    inp = synth.make_attention_inputs(cfg, seed=2)
+    out, lse = oracle.verify_attn(inp)
+    as_tree = dict(inp)
+    as_tree["tree_mask"] = np.concatenate([(np.uint32(2) << np.arange(n, dtype=np.uint32)) - np.uint32(1)
+                                           for n in np.diff(inp["q_indptr"])]).astype(np.uint32)
+    o2, l2 = oracle.verify_attn(as_tree)
+    assert np.array_equal(o2, out) and np.array_equal(l2, lse)
+
+
+def test_siblings_do_not_see_each_other_by_hand(oracle):
+    # D=1, one cached token (k=0, v=7) then root and two sibling drafts with k = v = (0, ln2, ln3), q = 1.
+    # Row 2 (second sibling) sees {old, root, itself}: weights (1, 1, 3)/5, NOT the first sibling.
+    kc = np.full((1, 1, 16, 1), np.nan, dtype=np.float32)
+    vc = np.full((1, 1, 16, 1), np.nan, dtype=np.float32)
+    kc[0, 0, :4, 0] = [0.0, 0.0, math.log(2), math.log(3)]
+    vc[0, 0, :4, 0] = [7.0, 1.0, 10.0, 100.0]
+    inp = dict(batch=1, num_q_heads=1, num_kv_heads=1, head_dim=1, block_size=16, num_blocks=1,
+               max_blocks_per_seq=1, total_rows=3, kv_dtype="f32", q_dtype="f32",
+               kv_len=np.array([4], np.int32), q_indptr=np.array([0, 3], np.int32),
+               block_table=np.array([[0]], np.int32), k_cache=kc, v_cache=vc, k_scale=None, v_scale=None,
+               q=np.ones((3, 1, 1), np.float32), sm_scale=1.0, tree_mask=np.array([0b001, 0b011, 0b101], np.uint32))
+    out, lse = oracle.verify_attn(inp)
+    ln2, ln3 = float(np.float32(math.log(2))), float(np.float32(math.log(3)))
+    assert out[0, 0, 0] == pytest.approx((7 + 1) / 2, abs=1e-14)
+    assert out[1, 0, 0] == pytest.approx((7 + 1 + 10 * math.exp(ln2)) / (2 + math.exp(ln2)), abs=1e-13)
+    assert out[2, 0, 0] == pytest.approx((7 + 1 + 100 * math.exp(ln3)) / (2 + math.exp(ln3)), abs=1e-13)
+    assert lse[2, 0] == pytest.approx(math.log(2 + math.exp(ln3)), abs=1e-14)
+
+
+def test_bad_tree_masks_rejected(oracle):
+    cfg = _small("f32", "f32", batch=2, ctx=("fixed", (20, 30)), depth=("fixed", 2))
+    inp = synth.make_attention_inputs(cfg, seed=0, tree=True)
+    for row, word in ((1, 0b001), (2, 0b1101), (3, 0)):   # own bit missing, a bit past the request, empty
+        bad = dict(inp)
+        bad["tree_mask"] = inp["tree_mask"].copy()
+        bad["tree_mask"][row] = word
+        with pytest.raises(ValueError):
+            oracle.verify_attn(bad)
 
 
 def test_prefix_consistency(oracle):
