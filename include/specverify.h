@@ -175,6 +175,30 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
                        void *stream);
 
 /*
+ * Greedy acceptance over draft trees (tree-structured drafts of the EAGLE family, the paper's draft
+ * model in Section 5.1; the output-preserving rule of Section 2.2 at temperature 0).  The new tokens of
+ * request b form a tree: node 0 is the last accepted token, node i in 1..k carries draft token
+ * draft_tokens[q_indptr[b]-b+i-1] and hangs under node tree_parent[q_indptr[b]+i] < i; target row i
+ * holds the logits that follow node i (computed by ss_spec_verify_attn with the matching tree_mask).
+ *     cur = 0; repeat: t = lowest-index argmax of target row cur; c = lowest-numbered child of cur
+ *     whose token is t; none: stop; else accept c, cur = c
+ *   out_tokens[b]      the accepted tokens, then t of the node where the walk stopped, then -1
+ *                      (SS_OUT_WIDTH entries): exactly what greedy decoding of the target emits
+ *   accepted_len[b]    number of accepted nodes n
+ *   accepted_nodes[b]  device int32 [batch][SS_MAX_DEPTH]: the accepted node numbers in path order,
+ *                      -1 beyond n (what a cache compaction needs)
+ *   tree_parent        device int32 [total_rows]; -1 for every request's node 0
+ * Other arguments, the workspace (ss_spec_accept_workspace) and errors as for ss_spec_accept.  Only the
+ * greedy rule is provided for trees: the sampled rule needs one residual distribution per rejected
+ * sibling, a chain of full-vocabulary passes this library does not implement.
+ */
+int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
+                                   int32_t total_rows, const int32_t *q_indptr, const int32_t *tree_parent,
+                                   const void *target_logits, const int32_t *draft_tokens, int32_t *accepted_len,
+                                   int32_t *out_tokens, int32_t *accepted_nodes, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * KV append, the step before verification (paper Section 3.4, Eq. 7: the decode KV is the prefill KV
  * with the new tokens' keys/values appended; Section 2.4: paged layout).  Request b's
  * q_len = q_indptr[b+1]-q_indptr[b] new tokens are written to the last q_len of its kv_len[b] cache

@@ -43,6 +43,7 @@ def _load():
         lib.oracle_encode.restype = None
         lib.oracle_kv_append.restype = ctypes.c_int
         lib.oracle_kv_commit.restype = ctypes.c_int
+        lib.oracle_tree_accept_greedy.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -116,6 +117,21 @@ def spec_accept(inp: Dict[str, object], *, greedy: Optional[bool] = None, tie_ep
         raise ValueError(f"oracle_spec_accept rejected its arguments (code {rc})")
     return dict(accepted_len=accepted, out_tokens=toks, ratio=ratio[:Rd], near_tie=near[:Rd],
                 y_lo=ylo, y_hi=yhi, resid_sum=rsum)
+
+
+def tree_accept_greedy(inp: Dict[str, object]) -> Dict[str, np.ndarray]:
+    """Greedy acceptance walk over the draft trees of a batch dict from ``synth.make_tree_accept_inputs``."""
+    B = inp["batch"]
+    accepted = np.full(B, -99, dtype=np.int32)
+    toks = np.full((B, OUT_WIDTH), -99, dtype=np.int32)
+    nodes = np.full((B, OUT_WIDTH - 1), -99, dtype=np.int32)
+    rc = _load().oracle_tree_accept_greedy(
+        ctypes.c_int(B), ctypes.c_int(inp["vocab"]), ctypes.c_int64(inp["row_stride"]),
+        ctypes.c_int(_DT[inp["logit_dtype"]]), _p(inp["q_indptr"]), _p(inp["tree_parent"]),
+        _p(inp["target_logits"]), _p(inp["draft_tokens"]), ctypes.c_int(OUT_WIDTH), _p(accepted), _p(toks), _p(nodes))
+    if rc != 0:
+        raise ValueError(f"oracle_tree_accept_greedy rejected its arguments (code {rc})")
+    return dict(accepted_len=accepted, out_tokens=toks, accepted_nodes=nodes)
 
 
 def encode(x: np.ndarray, dtype: str) -> np.ndarray:

@@ -445,6 +445,70 @@ int oracle_spec_accept(int B, int V, int64_t row_stride, int logit_dtype, const 
     return fail ? -5 : 0;
 }
 
+/* ---- greedy acceptance over a draft tree --------------------------------------
+ *
+ * The new tokens of request b form a tree: node 0 is the last accepted token,
+ * node i >= 1 carries draft token x_i (entry q_indptr[b]-b+i-1 of draft_tokens)
+ * and has parent tree_parent[q_indptr[b]+i] < i (-1 for node 0).  Target row i
+ * holds the logits that follow node i.  Greedy decoding emits, after any node,
+ * the lowest-index argmax of that node's row, so the walk is
+ *
+ *     cur = 0
+ *     repeat: t = argmax(row cur); c = the lowest-numbered child of cur with
+ *             x_c == t; if there is none stop, else accept c and set cur = c
+ *     emit the accepted tokens, then t (the argmax at the node where it stopped)
+ *
+ * and the output is exactly what plain greedy decoding of the target model
+ * would have produced.  accepted_nodes lists the accepted node numbers in path
+ * order (they are increasing), -1 beyond accepted_len.  A chain
+ * (tree_parent[i] = i-1) gives the greedy mode of oracle_spec_accept.
+ */
+int oracle_tree_accept_greedy(int B, int V, int64_t row_stride, int logit_dtype, const int32_t *q_indptr,
+                              const int32_t *tree_parent, const void *target_logits,
+                              const int32_t *draft_tokens, int out_width, int32_t *accepted_len,
+                              int32_t *out_tokens, int32_t *accepted_nodes)
+{
+    if (B < 0 || V <= 0 || row_stride < V || out_width < 1)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (k < 0 || k + 1 > out_width || tree_parent[q_indptr[b]] != -1)
+            return -4;
+        for (int i = 1; i <= k; ++i)
+            if (tree_parent[q_indptr[b] + i] < 0 || tree_parent[q_indptr[b] + i] >= i)
+                return -6;
+    }
+    for (int b = 0; b < B; ++b) {
+        int64_t row0 = q_indptr[b];
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        const int32_t *x = draft_tokens + (row0 - b) - 1; /* x[i] = token of node i, i = 1..k */
+        int32_t *toks = out_tokens + (int64_t)b * out_width;
+        int32_t *nodes = accepted_nodes + (int64_t)b * (out_width - 1);
+        for (int j = 0; j < out_width; ++j)
+            toks[j] = -1;
+        for (int j = 0; j < out_width - 1; ++j)
+            nodes[j] = -1;
+        int cur = 0, n = 0;
+        for (;;) {
+            int t = argmax_row(target_logits, (row0 + cur) * row_stride, V, logit_dtype);
+            int child = -1;
+            for (int i = cur + 1; i <= k && child < 0; ++i)
+                if (tree_parent[row0 + i] == cur && x[i] == t)
+                    child = i;
+            if (child < 0) {
+                toks[n] = t;
+                break;
+            }
+            toks[n] = t;
+            nodes[n] = child;
+            ++n;
+            cur = child;
+        }
+        accepted_len[b] = n;
+    }
+    return 0;
+}
+
 /* ---- KV append and commit (the steps around verification) --------------------
  *
  * Section 3.4, Eq. 7: the decode worker's KV is the prefill KV with every new

@@ -21,7 +21,7 @@ SS_OUT_WIDTH = 9
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_kv_append", "ss_kv_commit", "ss_depth_init",
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_kv_append", "ss_kv_commit", "ss_depth_init",
            "ss_depth_update", "ss_route_select", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
 
@@ -87,6 +87,10 @@ def lib() -> ctypes.CDLL:
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ss_kv_append.restype = ctypes.c_int32
+        L.ss_spec_accept_tree_greedy.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                                 ctypes.c_int32] + [ctypes.c_void_p] * 8 + [ctypes.c_size_t,
+                                                                                           ctypes.c_void_p]
+        L.ss_spec_accept_tree_greedy.restype = ctypes.c_int32
         L.ss_kv_append.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         L.ss_kv_commit.restype = ctypes.c_int32
@@ -177,6 +181,8 @@ def accept_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, objec
     d = dict(inp)
     for name in ("q_indptr", "target_logits", "draft_logits", "draft_tokens", "u_accept", "u_sample", "temperature"):
         d[name] = _to_dev(inp[name], device)
+    if inp.get("tree_parent") is not None:
+        d["tree_parent"] = _to_dev(inp["tree_parent"], device)
     return d
 
 
@@ -273,6 +279,15 @@ def ss_spec_accept(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens:
                                 _ptr(d["draft_tokens"]), _ptr(d["u_accept"]), _ptr(d["u_sample"]), _ptr(temp),
                                 ctypes.c_float(t_scalar), g, _ptr(accepted_len), _ptr(out_tokens), _ptr(ratio_out),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ss_spec_accept_tree_greedy(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,
+                               accepted_nodes: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(lib().ss_spec_accept_tree_greedy(d["batch"], d["vocab"], d["row_stride"], _DT[d["logit_dtype"]],
+                                            d["total_rows"], _ptr(d["q_indptr"]), _ptr(d["tree_parent"]),
+                                            _ptr(d["target_logits"]), _ptr(d["draft_tokens"]), _ptr(accepted_len),
+                                            _ptr(out_tokens), _ptr(accepted_nodes), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream()))
 
 
 def alloc_accept_outputs(d: Dict[str, object], device="cuda:0"):

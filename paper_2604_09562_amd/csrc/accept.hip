@@ -399,6 +399,31 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
     __syncthreads();
     if (wave != 0) return;
 
+    if (a.tree_parent) {
+        // Greedy walk over a draft tree: lane i holds node i (1..k) with its parent and token; each
+        // step a ballot finds the lowest-numbered child of the current node that carries the token
+        // greedy decoding emits there.
+        const int par = (lane >= 1 && lane <= k) ? a.tree_parent[t0 + lane] : -2;
+        const int x = (lane >= 1 && lane <= k) ? a.draft_tokens[d0 + lane - 1] : -1;
+        int cur = 0, n = 0, my_tok = -1, my_node = -1;
+        for (;;) {   // at most k steps: every step moves to a higher-numbered node
+            const int t = row_arg[cur];
+            const unsigned long long hit = __ballot(par == cur && x == t);
+            if (!hit) break;
+            cur = __ffsll((long long)hit) - 1;
+            if (lane == n) {
+                my_tok = t;
+                my_node = cur;
+            }
+            ++n;
+        }
+        if (lane == n) my_tok = row_arg[cur];
+        if (lane < SS_OUT_WIDTH) a.out_tokens[(int64_t)b * SS_OUT_WIDTH + lane] = my_tok;
+        if (lane < SS_MAX_DEPTH) a.accepted_nodes[(int64_t)b * SS_MAX_DEPTH + lane] = my_node;
+        if (lane == 0) a.accepted_len[b] = n;
+        return;
+    }
+
     // every draft in parallel: lane i judges draft i
     bool reject = false;
     int x = -1;

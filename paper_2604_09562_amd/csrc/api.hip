@@ -198,6 +198,46 @@ size_t ss_spec_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab
     return accept_workspace_bytes(batch, total_rows, vocab);
 }
 
+int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
+                                   int32_t total_rows, const int32_t *q_indptr, const int32_t *tree_parent,
+                                   const void *target_logits, const int32_t *draft_tokens, int32_t *accepted_len,
+                                   int32_t *out_tokens, int32_t *accepted_nodes, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
+    if (batch == 0) return SS_OK;
+    if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
+    if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
+        return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
+    const int64_t esz = logit_dtype == SS_F32 ? 4 : 2;
+    if (!q_indptr || !tree_parent || !target_logits || !accepted_len || !out_tokens || !accepted_nodes)
+        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (total_rows > batch && !draft_tokens)
+        return fail(SS_ERR_INVALID_ARG, "draft_tokens must be given when any request has drafts");
+    if (!aligned16(target_logits) || (row_stride * esz) % 16)
+        return fail(SS_ERR_INVALID_ARG, "logits rows must start 16-byte aligned (base and row_stride)");
+    const size_t need = accept_workspace_bytes(batch, total_rows, vocab);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
+    if (workspace_bytes < need)
+        return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (g_validate) {
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, 0,
+                                    static_cast<hipStream_t>(stream), "ss_spec_accept_tree_greedy");
+        if (rc == SS_OK)
+            rc = validate_accept(draft_tokens, nullptr, nullptr, nullptr, batch, total_rows - batch, vocab, 1,
+                                 static_cast<hipStream_t>(stream), "ss_spec_accept_tree_greedy");
+        if (rc != SS_OK) return rc;
+    }
+    AcceptArgs a{};
+    a.batch = batch; a.vocab = vocab; a.logit_dtype = logit_dtype; a.total_rows = total_rows; a.greedy = 1;
+    a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft_tokens = draft_tokens;
+    a.accepted_len = accepted_len; a.out_tokens = out_tokens; a.workspace = workspace;
+    a.tree_parent = tree_parent; a.accepted_nodes = accepted_nodes;
+    return accept_launch(a, static_cast<hipStream_t>(stream));
+}
+
 int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
                        const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
                        const int32_t *draft_tokens, const float *u_accept, const float *u_sample,

@@ -82,6 +82,9 @@ struct AcceptArgs {
     int32_t *accepted_len, *out_tokens;
     float *ratio_out;
     void *workspace;
+    // greedy walk over draft trees (both NULL for chains)
+    const int32_t *tree_parent;   // per target row: parent node within the request, -1 for node 0
+    int32_t *accepted_nodes;      // [batch][SS_MAX_DEPTH]
 };
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream);

@@ -357,6 +357,43 @@ def make_accept_inputs(cfg: VerifyConfig, seed: int = 0, *, depth: Optional[np.n
     )
 
 
+def make_tree_accept_inputs(cfg: VerifyConfig, seed: int = 0, *, depth: Optional[np.ndarray] = None,
+                            hit: float = 0.6, row_pad: int = 0) -> Dict[str, object]:
+    """A batch for greedy acceptance over draft trees.
+
+    Target logits, layout and sizes are those of ``make_accept_inputs``; the drafts of a request
+    form the random tree of ``draw_draft_trees`` (the same tree ``make_attention_inputs(tree=True)``
+    draws for these depths and seed).  A draft node carries, with probability ``hit``, the token
+    greedy decoding would emit after its parent (the lowest-index maximum of the parent's stored
+    target row), as a good draft model's candidates do; otherwise, with probability 0.15, a copy of
+    an earlier sibling's token, and else a uniformly random token.
+    """
+    inp = make_accept_inputs(cfg, seed, depth=depth, greedy=True, row_pad=row_pad)
+    q_indptr, V = inp["q_indptr"], inp["vocab"]
+    r = _rng(cfg, seed, 11)
+    parent, mask = draw_draft_trees(q_indptr, _rng(cfg, seed, 10))
+    tgt_val = decode_storage(inp["target_logits"], cfg.logit_dtype)[:, :V]
+    best = np.argmax(tgt_val, axis=1)
+    tokens = np.zeros(len(inp["draft_tokens"]), dtype=np.int32)
+    for b in range(inp["batch"]):
+        r0, n = int(q_indptr[b]), int(q_indptr[b + 1] - q_indptr[b])
+        node_tok = [-1] * n
+        for i in range(1, n):
+            p = int(parent[r0 + i])
+            sibs = [node_tok[j] for j in range(1, i) if parent[r0 + j] == p]
+            u = r.random()
+            if u < hit:
+                node_tok[i] = int(best[r0 + p])
+            elif u < hit + 0.15 and sibs:
+                node_tok[i] = sibs[int(r.integers(0, len(sibs)))]
+            else:
+                node_tok[i] = int(r.integers(0, V))
+            tokens[r0 - b + i - 1] = node_tok[i]
+    inp["draft_tokens"] = tokens
+    inp["tree_parent"], inp["tree_mask"] = parent, mask
+    return inp
+
+
 def decode_storage(x: np.ndarray, dtype: str) -> np.ndarray:
     """Storage -> float32 via torch (generator-side helper for drawing draft tokens and for tests)."""
     if dtype == "f32":

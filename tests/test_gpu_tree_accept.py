@@ -1,0 +1,82 @@
+"""GPU parity of ss_spec_accept_tree_greedy against the CPU oracle: token ids, lengths and paths are exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_09562_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
+
+
+def run_gpu(inp):
+    d = binding.accept_to_device({**inp, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
+    acc, toks, _, ws = binding.alloc_accept_outputs(d)
+    nodes = torch.full((inp["batch"], 8), -77, dtype=torch.int32, device="cuda:0")
+    ws.fill_(0xFF)
+    binding.ss_spec_accept_tree_greedy(d, acc, toks, nodes, ws)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), toks.cpu().numpy(), nodes.cpu().numpy()
+
+
+def compare(inp, oracle, label):
+    ref = oracle.tree_accept_greedy(inp)
+    acc, toks, nodes = run_gpu(inp)
+    assert np.array_equal(acc, ref["accepted_len"]), label
+    assert np.array_equal(toks, ref["out_tokens"]), label
+    assert np.array_equal(nodes, ref["accepted_nodes"]), label
+    return ref
+
+
+@pytest.mark.parametrize("logit_dtype", ["f32", "bf16"])
+def test_tiny_and_odd_vocabularies(oracle, logit_dtype):
+    for vocab in (32000, 997, 8192, 50257):
+        pad = (-vocab) % (8 if logit_dtype == "bf16" else 4)   # rows must start 16-byte aligned
+        cfg = TINY.scaled(batch=9, vocab=vocab, logit_dtype=logit_dtype, depth=("uniform", 0, 8))
+        inp = synth.make_tree_accept_inputs(cfg, seed=vocab % 7, row_pad=pad)
+        compare(inp, oracle, f"vocab {vocab} {logit_dtype}")
+
+
+def test_full_vocabulary_batch(oracle):
+    cfg = RAGGED.scaled(batch=48)
+    inp = synth.make_tree_accept_inputs(cfg, seed=1)
+    ref = compare(inp, oracle, "ragged 128k vocabulary")
+    assert ref["accepted_len"].max() >= 3 and ref["accepted_len"].min() == 0
+
+
+def test_chain_parents_equal_the_chain_entry_point(oracle):
+    cfg = LLAMA8B.scaled(batch=16, depth=("uniform", 0, 8))
+    inp = synth.make_accept_inputs(cfg, seed=2, greedy=True)
+    inp["tree_parent"] = np.concatenate([np.arange(-1, k) for k in inp["depth"]]).astype(np.int32)
+    acc, toks, nodes = run_gpu(inp)
+    d = binding.accept_to_device(inp)
+    acc2, toks2, _, ws = binding.alloc_accept_outputs(d)
+    binding.ss_spec_accept(d, acc2, toks2, None, ws, greedy=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc, acc2.cpu().numpy()) and np.array_equal(toks, toks2.cpu().numpy())
+    compare(inp, oracle, "chain as tree")
+
+
+def test_ties_and_duplicate_siblings(oracle):
+    # equal maxima in a row (lowest index wins) and siblings with the same token (lowest node wins)
+    cfg = TINY.scaled(batch=12, vocab=4099, logit_dtype="bf16", depth=("fixed", 8))
+    inp = synth.make_tree_accept_inputs(cfg, seed=4, hit=0.8, row_pad=(-4099) % 8)
+    t = inp["target_logits"]
+    for r in range(t.shape[0]):
+        row = synth.decode_storage(t[r:r + 1], "bf16")[0, :4099]
+        j = int(np.argmax(row))
+        t[r, (j + 1234) % 4099] = t[r, j]          # a second, equal maximum elsewhere in the row
+    compare(inp, oracle, "ties")
+
+
+def test_argument_errors():
+    cfg = TINY.scaled(batch=2, depth=("fixed", 2))
+    inp = synth.make_tree_accept_inputs(cfg, seed=0)
+    d = binding.accept_to_device({**inp, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
+    acc, toks, _, ws = binding.alloc_accept_outputs(d)
+    nodes = torch.zeros((2, 8), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(binding.SpecVerifyError):
+        binding.ss_spec_accept_tree_greedy({**d, "tree_parent": None}, acc, toks, nodes, ws)
+    with pytest.raises(binding.SpecVerifyError):
+        binding.ss_spec_accept_tree_greedy(d, acc, toks, nodes, ws[:256])
