@@ -221,6 +221,26 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
                      int32_t new_dtype, int32_t total_rows, void *stream);
 
 /*
+ * Compaction after acceptance over a draft tree (between ss_spec_accept_tree_greedy and ss_kv_commit).
+ * The q_len new tokens of request b sit at cache positions P+i, P = kv_len[b]-q_len, i = node number.
+ * Its accepted path accepted_nodes[b][0..n-1] = a_1 < .. < a_n (n = accepted_len[b]) is moved to
+ * positions P+1 .. P+n, where a chain would have put it, so that ss_kv_commit's length rule applies
+ * unchanged: in path order, if a_j != j the key and value of every KV head move from position P+a_j to
+ * P+j.  Storage is copied as it is, except e4m3 bytes whose source and destination lie in different
+ * blocks: byte' = nearest e4m3fn (ties to even) of clamp((decode(byte) * scale_src) / scale_dst, +-448),
+ * product and quotient one float32 operation each.  No scale changes; all other slots, the rejected
+ * ones included, keep their contents.  For a chain (a_j = j) nothing moves.
+ *   kv, batch       as for ss_kv_append (kv_len still counts all q_len new tokens; the cache is WRITTEN)
+ *   accepted_nodes  device int32 [batch][SS_MAX_DEPTH], as written by ss_spec_accept_tree_greedy
+ *   accepted_len    device int32 [batch]
+ * A row of accepted_nodes that is not increasing within 1..q_len-1 ends that request's moves at the
+ * offending entry (nothing outside the request's new slots is ever touched).
+ * Errors: SS_ERR_INVALID_ARG (NULL pointers, bad dtypes or sizes), SS_ERR_DEVICE (launch failure).
+ */
+int32_t ss_kv_compact(const ss_paged_kv *kv, const ss_batch *batch, const int32_t *accepted_nodes,
+                      const int32_t *accepted_len, int32_t total_rows, void *stream);
+
+/*
  * Commit after acceptance (same passage): request b keeps its accepted_len[b] accepted drafts, so its
  * valid cache length becomes kv_len[b] - k_b + accepted_len[b] with k_b = q_indptr[b+1]-q_indptr[b]-1;
  * the rejected slots fall past the end (no data moves), and the token the acceptance step drew is

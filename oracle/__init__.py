@@ -44,6 +44,7 @@ def _load():
         lib.oracle_kv_append.restype = ctypes.c_int
         lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_tree_accept_greedy.restype = ctypes.c_int
+        lib.oracle_kv_compact.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -151,6 +152,19 @@ def kv_append(inp: Dict[str, object]) -> None:
         _p(inp["kv_len"]), _p(inp["q_indptr"]), ctypes.c_int(_DT[inp["new_dtype"]]), _p(inp["k_new"]), _p(inp["v_new"]))
     if rc != 0:
         raise ValueError(f"oracle_kv_append rejected its arguments (code {rc})")
+
+
+def kv_compact(inp: Dict[str, object], accepted_nodes: np.ndarray, accepted_len: np.ndarray) -> None:
+    """Move the accepted tree path of every request to the slots a chain would occupy, in place."""
+    nodes = np.ascontiguousarray(accepted_nodes, dtype=np.int32)
+    rc = _load().oracle_kv_compact(
+        ctypes.c_int(inp["batch"]), ctypes.c_int(inp["num_kv_heads"]), ctypes.c_int(inp["head_dim"]),
+        ctypes.c_int(inp["block_size"]), ctypes.c_int(inp["max_blocks_per_seq"]), ctypes.c_int(_DT[inp["kv_dtype"]]),
+        _p(inp["k_cache"]), _p(inp["v_cache"]), _p(inp["k_scale"]), _p(inp["v_scale"]), _p(inp["block_table"]),
+        _p(inp["kv_len"]), _p(inp["q_indptr"]), _p(nodes), ctypes.c_int(nodes.shape[1]),
+        _p(np.ascontiguousarray(accepted_len, dtype=np.int32)))
+    if rc != 0:
+        raise ValueError(f"oracle_kv_compact rejected its arguments (code {rc})")
 
 
 def kv_commit(q_indptr: np.ndarray, accepted_len: np.ndarray, kv_len: np.ndarray) -> np.ndarray:

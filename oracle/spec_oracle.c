@@ -640,6 +640,69 @@ int oracle_kv_commit(int B, const int32_t *q_indptr, const int32_t *accepted_len
     return 0;
 }
 
+/* Compaction after acceptance over a draft tree.  The q_len new tokens of request b sit at
+ * positions P+i (P = kv_len - q_len, i = node number).  The accepted path a_1 < a_2 < .. < a_n
+ * (accepted_nodes, row width nodes_width) must end up at positions P+1 .. P+n, where a chain would
+ * have put it, so that oracle_kv_commit's length rule applies unchanged: for j = 1..n in this order,
+ * if a_j != j the key/value of every head moves from position P+a_j to position P+j (a_j >= j, and a
+ * later move never reads a slot an earlier one wrote).  Storage is copied as it is, except in e4m3
+ * caches when source and destination lie in different blocks, whose scales differ: then
+ *     byte' = nearest e4m3fn (ties to even) of clamp((decode(byte) * s_src) / s_dst, +-448),
+ * product and quotient each one float32 operation.  No scale changes.  Everything else in the cache,
+ * the rejected slots included, is left as it was.
+ */
+int oracle_kv_compact(int B, int Hkv, int D, int bs, int max_blocks, int kv_dtype, void *k_cache, void *v_cache,
+                      const float *k_scale, const float *v_scale, const int32_t *block_table, const int32_t *kv_len,
+                      const int32_t *q_indptr, const int32_t *accepted_nodes, int nodes_width,
+                      const int32_t *accepted_len)
+{
+    if (B < 0 || Hkv <= 0 || D <= 0 || bs <= 0 || nodes_width < 0) return -1;
+    if (kv_dtype == OR_FP8_E4M3 && (!k_scale || !v_scale)) return -2;
+    for (int b = 0; b < B; ++b) {
+        int q_len = q_indptr[b + 1] - q_indptr[b], L = kv_len[b], n = accepted_len[b];
+        if (q_len < 1 || L < q_len || (L + bs - 1) / bs > max_blocks) return -3;
+        if (n < 0 || n > q_len - 1 || n > nodes_width) return -4;
+        for (int j = 1; j <= n; ++j) {
+            int a = accepted_nodes[(int64_t)b * nodes_width + j - 1];
+            int prev = j > 1 ? accepted_nodes[(int64_t)b * nodes_width + j - 2] : 0;
+            if (a <= prev || a > q_len - 1) return -6;
+        }
+    }
+    size_t esz = kv_dtype == OR_F32 ? 4 : kv_dtype == OR_BF16 ? 2 : 1;
+    for (int side = 0; side < 2; ++side) {
+        char *cache = (char *)(side ? v_cache : k_cache);
+        const float *scale = side ? v_scale : k_scale;
+        for (int b = 0; b < B; ++b) {
+            int q_len = q_indptr[b + 1] - q_indptr[b], P = kv_len[b] - q_len;
+            for (int j = 1; j <= accepted_len[b]; ++j) {
+                int a = accepted_nodes[(int64_t)b * nodes_width + j - 1];
+                if (a == j) continue;
+                int ps = P + a, pd = P + j;
+                int64_t bs_src = block_table[(int64_t)b * max_blocks + ps / bs];
+                int64_t bs_dst = block_table[(int64_t)b * max_blocks + pd / bs];
+                for (int h = 0; h < Hkv; ++h) {
+                    int64_t src = ((bs_src * Hkv + h) * bs + ps % bs) * (int64_t)D;
+                    int64_t dst = ((bs_dst * Hkv + h) * bs + pd % bs) * (int64_t)D;
+                    if (kv_dtype != OR_FP8_E4M3 || bs_src == bs_dst) {
+                        memmove(cache + dst * esz, cache + src * esz, esz * (size_t)D);
+                        continue;
+                    }
+                    float s_src = scale[bs_src * Hkv + h], s_dst = scale[bs_dst * Hkv + h];
+                    for (int d = 0; d < D; ++d) {
+                        float x = (float)decode_e4m3fn(((uint8_t *)cache)[src + d]);
+                        float y = x * s_src;
+                        float q = y / s_dst;
+                        if (q > 448.0f) q = 448.0f;
+                        if (q < -448.0f) q = -448.0f;
+                        ((uint8_t *)cache)[dst + d] = isnan(q) ? 0x7F : encode_e4m3fn(q);
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
 /* for tests: the two storage encoders on arrays */
 void oracle_encode(const float *src, int64_t n, int dtype, void *dst)
 {

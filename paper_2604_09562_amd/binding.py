@@ -21,7 +21,7 @@ SS_OUT_WIDTH = 9
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_kv_append", "ss_kv_commit", "ss_depth_init",
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_kv_append", "ss_kv_compact", "ss_kv_commit", "ss_depth_init",
            "ss_depth_update", "ss_route_select", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
 
@@ -94,6 +94,9 @@ def lib() -> ctypes.CDLL:
         L.ss_kv_append.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         L.ss_kv_commit.restype = ctypes.c_int32
+        L.ss_kv_compact.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+        L.ss_kv_compact.restype = ctypes.c_int32
         L.ss_kv_commit.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.ss_depth_init.restype = ctypes.c_int32
         L.ss_depth_init.argtypes = [ctypes.POINTER(ss_depth_state)]
@@ -229,6 +232,13 @@ def ss_kv_append(d: Dict[str, object]) -> None:
     kv, bt = _descriptors(d, 0)
     _check(lib().ss_kv_append(ctypes.byref(kv), ctypes.byref(bt), _ptr(d["k_new"]), _ptr(d["v_new"]),
                               _DT[d["new_dtype"]], d["total_rows"], _stream()))
+
+
+def ss_kv_compact(d: Dict[str, object], accepted_nodes: torch.Tensor, accepted_len: torch.Tensor) -> None:
+    """Enqueue the move of every request's accepted tree path to the slots a chain would occupy (cache in place)."""
+    kv, bt = _descriptors(d, 0)
+    _check(lib().ss_kv_compact(ctypes.byref(kv), ctypes.byref(bt), _ptr(accepted_nodes), _ptr(accepted_len),
+                               d["total_rows"], _stream()))
 
 
 def ss_kv_commit(q_indptr: torch.Tensor, accepted_len: torch.Tensor, kv_len: torch.Tensor) -> None:

@@ -283,9 +283,10 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     return accept_launch(a, static_cast<hipStream_t>(stream));
 }
 
-int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k_new, const void *v_new,
-                     int32_t new_dtype, int32_t total_rows, void *stream)
+// Host-visible checks shared by the calls that write the cache; *empty is set for a batch of zero requests.
+static int32_t check_kv_write(const ss_paged_kv *kv, const ss_batch *batch, int32_t total_rows, bool *empty)
 {
+    *empty = false;
     if (!kv || !batch) return fail(SS_ERR_INVALID_ARG, "kv and batch descriptors must not be NULL");
     if (kv->block_size != SS_BLOCK_SIZE)
         return fail(SS_ERR_INVALID_ARG, "block_size must be %d, got %d", SS_BLOCK_SIZE, kv->block_size);
@@ -293,32 +294,67 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
         return fail(SS_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", kv->head_dim);
     if (kv->num_kv_heads <= 0 || kv->num_blocks < 0) return fail(SS_ERR_INVALID_ARG, "bad num_kv_heads or num_blocks");
     if (kv->dtype < SS_F32 || kv->dtype > SS_FP8_E4M3) return fail(SS_ERR_INVALID_ARG, "unknown KV dtype %d", kv->dtype);
-    if (new_dtype != SS_F32 && new_dtype != SS_BF16) return fail(SS_ERR_INVALID_ARG, "new_dtype must be SS_F32 or SS_BF16");
     if (batch->batch < 0 || total_rows < batch->batch || (int64_t)total_rows > (int64_t)batch->batch * SS_OUT_WIDTH)
         return fail(SS_ERR_INVALID_ARG, "total_rows (%d) must lie in [batch, %d*batch] for batch %d", total_rows,
                     SS_OUT_WIDTH, batch->batch);
-    if (batch->batch == 0) return SS_OK;
+    if (batch->batch == 0) {
+        *empty = true;
+        return SS_OK;
+    }
     if (batch->max_blocks_per_seq <= 0) return fail(SS_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
     if ((int64_t)batch->batch * SS_OUT_WIDTH * kv->num_kv_heads > 0x7fffffffll)
         return fail(SS_ERR_UNSUPPORTED, "batch * kv heads too large for one launch");
-    if (!kv->k || !kv->v || !batch->block_table || !batch->kv_len || !batch->q_indptr || !k_new || !v_new)
+    if (!kv->k || !kv->v || !batch->block_table || !batch->kv_len || !batch->q_indptr)
         return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
     if ((kv->dtype == SS_FP8_E4M3) != (kv->k_scale != nullptr) || (kv->k_scale != nullptr) != (kv->v_scale != nullptr))
         return fail(SS_ERR_INVALID_ARG, "k_scale/v_scale must both be given for fp8 caches and be NULL otherwise");
-    if (g_validate) {
-        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
-                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
-                                          static_cast<hipStream_t>(stream), "ss_kv_append");
-        if (rc != SS_OK) return rc;
-    }
+    return SS_OK;
+}
+
+static KvAppendArgs kv_write_args(const ss_paged_kv *kv, const ss_batch *batch)
+{
     KvAppendArgs a{};
     a.k = const_cast<void *>(kv->k); a.v = const_cast<void *>(kv->v);
     a.k_scale = const_cast<float *>(kv->k_scale); a.v_scale = const_cast<float *>(kv->v_scale);
     a.num_kv_heads = kv->num_kv_heads; a.head_dim = kv->head_dim; a.kv_dtype = kv->dtype;
     a.batch = batch->batch; a.max_blocks = batch->max_blocks_per_seq;
     a.block_table = batch->block_table; a.kv_len = batch->kv_len; a.q_indptr = batch->q_indptr;
+    return a;
+}
+
+int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k_new, const void *v_new,
+                     int32_t new_dtype, int32_t total_rows, void *stream)
+{
+    bool empty;
+    const int32_t rc0 = check_kv_write(kv, batch, total_rows, &empty);
+    if (rc0 != SS_OK || empty) return rc0;
+    if (new_dtype != SS_F32 && new_dtype != SS_BF16) return fail(SS_ERR_INVALID_ARG, "new_dtype must be SS_F32 or SS_BF16");
+    if (!k_new || !v_new) return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (g_validate) {
+        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
+                                          static_cast<hipStream_t>(stream), "ss_kv_append");
+        if (rc != SS_OK) return rc;
+    }
+    KvAppendArgs a = kv_write_args(kv, batch);
     a.k_new = k_new; a.v_new = v_new; a.new_dtype = new_dtype;
     return kv_append_launch(a, static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_kv_compact(const ss_paged_kv *kv, const ss_batch *batch, const int32_t *accepted_nodes,
+                      const int32_t *accepted_len, int32_t total_rows, void *stream)
+{
+    bool empty;
+    const int32_t rc0 = check_kv_write(kv, batch, total_rows, &empty);
+    if (rc0 != SS_OK || empty) return rc0;
+    if (!accepted_nodes || !accepted_len) return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (g_validate) {
+        const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
+                                          static_cast<hipStream_t>(stream), "ss_kv_compact");
+        if (rc != SS_OK) return rc;
+    }
+    return kv_compact_launch(kv_write_args(kv, batch), accepted_nodes, accepted_len, static_cast<hipStream_t>(stream));
 }
 
 int32_t ss_kv_commit(int32_t batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len, void *stream)

@@ -100,6 +100,8 @@ struct KvAppendArgs {
     int32_t new_dtype;
 };
 int32_t kv_append_launch(const KvAppendArgs &a, hipStream_t stream);
+int32_t kv_compact_launch(const KvAppendArgs &a, const int32_t *accepted_nodes, const int32_t *accepted_len,
+                          hipStream_t stream);   // k_new/v_new/new_dtype of the arguments are not used
 int32_t kv_commit_launch(int batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len,
                          hipStream_t stream);
 

@@ -1,7 +1,9 @@
-// KV append before the verify step and commit after acceptance (decode KV = prefill KV with the new
-// tokens appended).  One wavefront per (request, new token, KV head); a lane owns head_dim/64
+// KV append before the verify step, compaction of an accepted tree path and commit after acceptance
+// (decode KV = prefill KV with the new tokens appended).  One wavefront per (request, new token, KV head); a lane owns head_dim/64
 // consecutive elements of the key and of the value.
 #include "common.h"
+
+#include <type_traits>
 
 namespace ss {
 namespace {
@@ -102,6 +104,56 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(int batch, const int32_t
     kv_len[b] = kv_len[b] - k + accepted_len[b];   // the accepted drafts stay, the rejected slots fall past the end
 }
 
+// Compaction after acceptance over a draft tree: the accepted nodes a_1 < .. < a_n of a request move
+// from cache positions P + a_j to P + j, where a chain would have put them.  grid: batch * kv heads,
+// one wavefront each; a lane owns the same EPL elements of every token row, and walks the moves in
+// path order, so its own loads and stores keep the order the moves need (a_j >= j: a move never reads
+// a slot that an earlier one wrote).  e4m3 bytes that change block are rescaled from the source
+// block's scale to the destination's.
+template <int KV_DT, int EPL>
+__global__ __launch_bounds__(64) void kv_compact_kernel(KvAppendArgs a, const int32_t *accepted_nodes,
+                                                        const int32_t *accepted_len)
+{
+    typedef typename std::conditional<KV_DT == SS_F32, float,
+                                      typename std::conditional<KV_DT == SS_BF16, uint16_t, uint8_t>::type>::type elem_t;
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x % a.num_kv_heads, b = blockIdx.x / a.num_kv_heads;
+    const int q_len = a.q_indptr[b + 1] - a.q_indptr[b];
+    const int P = a.kv_len[b] - q_len;
+    const int n = min(accepted_len[b], q_len - 1);
+    const int D = a.head_dim;
+    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks;
+    int prev = 0;
+    for (int j = 1; j <= n; ++j) {
+        const int node = accepted_nodes[(int64_t)b * SS_MAX_DEPTH + j - 1];
+        if (node <= prev || node >= q_len) break;   // not a path: leave the rest alone
+        prev = node;
+        if (node == j) continue;
+        const int ps = P + node, pd = P + j;
+        const int64_t blk_s = bt[ps / kTile], blk_d = bt[pd / kTile];
+        const int64_t src = ((blk_s * a.num_kv_heads + h) * kTile + ps % kTile) * D + lane * EPL;
+        const int64_t dst = ((blk_d * a.num_kv_heads + h) * kTile + pd % kTile) * D + lane * EPL;
+#pragma unroll
+        for (int side = 0; side < 2; ++side) {
+            elem_t *cache = static_cast<elem_t *>(side ? a.v : a.k);
+            elem_t x[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) x[e] = cache[src + e];
+            if constexpr (KV_DT == SS_FP8_E4M3) {
+                if (blk_s != blk_d) {
+                    const float *scales = side ? a.v_scale : a.k_scale;
+                    const float s_src = scales[blk_s * a.num_kv_heads + h], s_dst = scales[blk_d * a.num_kv_heads + h];
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e)
+                        x[e] = to_e4m3_rne(__builtin_amdgcn_cvt_f32_fp8((uint32_t)x[e], 0) * s_src, s_dst);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) cache[dst + e] = x[e];
+        }
+    }
+}
+
 template <int KV_DT, int NEW_DT>
 int32_t launch_append(const KvAppendArgs &a, hipStream_t stream)
 {
@@ -131,6 +183,29 @@ int32_t kv_append_launch(const KvAppendArgs &a, hipStream_t stream)
     case SS_BF16: return launch_append_kv<SS_BF16>(a, stream);
     default: return launch_append_kv<SS_FP8_E4M3>(a, stream);
     }
+}
+
+int32_t kv_compact_launch(const KvAppendArgs &a, const int32_t *accepted_nodes, const int32_t *accepted_len,
+                          hipStream_t stream)
+{
+    if (a.batch == 0) return SS_OK;
+    const dim3 grid((unsigned)a.batch * a.num_kv_heads), wg(64);
+    const bool wide = a.head_dim == 128;
+    switch (a.kv_dtype) {
+    case SS_F32:
+        if (wide) hipLaunchKernelGGL((kv_compact_kernel<SS_F32, 2>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+        else hipLaunchKernelGGL((kv_compact_kernel<SS_F32, 1>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+        break;
+    case SS_BF16:
+        if (wide) hipLaunchKernelGGL((kv_compact_kernel<SS_BF16, 2>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+        else hipLaunchKernelGGL((kv_compact_kernel<SS_BF16, 1>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+        break;
+    default:
+        if (wide) hipLaunchKernelGGL((kv_compact_kernel<SS_FP8_E4M3, 2>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+        else hipLaunchKernelGGL((kv_compact_kernel<SS_FP8_E4M3, 1>), grid, wg, 0, stream, a, accepted_nodes, accepted_len);
+    }
+    SS_HIP_CHECK(hipGetLastError(), "launch kv_compact_kernel");
+    return SS_OK;
 }
 
 int32_t kv_commit_launch(int batch, const int32_t *q_indptr, const int32_t *accepted_len, int32_t *kv_len,
