@@ -90,8 +90,8 @@ typedef struct ss_paged_kv {
  *                library pick a kernel with fewer padded query rows; a bound that some request
  *                exceeds is a caller error (rows beyond it are not computed).
  *   tree_mask    NULL: the new tokens of a request form a chain (row i attends new tokens 0..i).
- *                Otherwise device uint32 [total rows]: the new tokens form a draft tree (tree-structured
- *                drafts as in the EAGLE family the paper's Section 5.1 uses as its draft model) with row 0
+ *                Otherwise device uint32 [total rows]: the new tokens form a draft tree (the dynamic
+ *                draft trees of the speculative systems the paper builds on, Section 2.2) with row 0
  *                the root; bit j of a row's word says that the row attends new token j of its own request
  *                (position kv_len-q_len+j), i.e. that node j is the row's own node or an ancestor of it.
  *                Every row's own bit must be set and no bit at or above q_len; the context before the new
@@ -175,8 +175,8 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
                        void *stream);
 
 /*
- * Greedy acceptance over draft trees (tree-structured drafts of the EAGLE family, the paper's draft
- * model in Section 5.1; the output-preserving rule of Section 2.2 at temperature 0).  The new tokens of
+ * Greedy acceptance over draft trees (Section 2.2: dynamic draft trees, verified in one parallel
+ * pass with the target's output preserved; here at temperature 0).  The new tokens of
  * request b form a tree: node 0 is the last accepted token, node i in 1..k carries draft token
  * draft_tokens[q_indptr[b]-b+i-1] and hangs under node tree_parent[q_indptr[b]+i] < i; target row i
  * holds the logits that follow node i (computed by ss_spec_verify_attn with the matching tree_mask).
