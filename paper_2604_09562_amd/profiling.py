@@ -26,9 +26,9 @@ def kernel_table(db_path: str) -> str:
     rows = c.execute("select name, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
                      "from kernels group by name order by 6 desc").fetchall()
     tot = sum(r[5] for r in rows) or 1
-    out = [f"{'kernel':78s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
+    out = [f"{'kernel':96s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
     for n, k, a, mi, ma, s in rows:
-        out.append(f"{n[:78]:78s} {k:6d} {a / 1e3:9.2f} {mi / 1e3:9.2f} {ma / 1e3:9.2f} {100 * s / tot:6.2f}")
+        out.append(f"{n[:96]:96s} {k:6d} {a / 1e3:9.2f} {mi / 1e3:9.2f} {ma / 1e3:9.2f} {100 * s / tot:6.2f}")
     return "\n".join(out)
 
 
