@@ -115,7 +115,7 @@ def main() -> int:
 
     def step(i: int) -> None:
         binding.ss_spec_verify_attn(d_att[i % nrot], out, lse, ws_att, max_q_len=max_q_len)
-        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc)
+        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc, max_q_len=max_q_len)
 
     for i in range(args.warmup):
         step(i)
@@ -138,7 +138,7 @@ def main() -> int:
         ev[0].record()
         binding.ss_spec_verify_attn(d_att[i % nrot], out, lse, ws_att, max_q_len=max_q_len)
         ev[1].record()
-        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc)
+        binding.ss_spec_accept(d_acc[i % nrot], n_acc, toks, None, ws_acc, max_q_len=max_q_len)
         ev[2].record()
         torch.cuda.synchronize()
         t_att.append(ev[0].elapsed_time(ev[1]))
@@ -147,7 +147,7 @@ def main() -> int:
     g_acc, g_toks = torch.empty_like(n_acc), torch.empty_like(toks)
     for i in range(6):
         ev[0].record()
-        binding.ss_spec_accept(d_acc[i % nrot], g_acc, g_toks, None, ws_acc, greedy=True)
+        binding.ss_spec_accept(d_acc[i % nrot], g_acc, g_toks, None, ws_acc, greedy=True, max_q_len=max_q_len)
         ev[1].record()
         torch.cuda.synchronize()
         t_greedy.append(ev[0].elapsed_time(ev[1]))

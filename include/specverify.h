@@ -116,8 +116,9 @@ const char *ss_last_error(void);
 
 /*
  * Bytes of device workspace ss_spec_verify_attn needs for this shape (256-byte aligned
- * buffer).  Depends only on the host-visible fields, not on device contents.  Returns 0 and
- * sets the error message if the arguments are invalid.
+ * buffer).  Depends only on the host-visible fields, not on device contents (batch->max_q_len
+ * included: a workspace sized for a larger bound, or for 0, also serves calls with a smaller one).
+ * Returns 0 and sets the error message if the arguments are invalid.
  */
 size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batch, int32_t num_q_heads,
                                      int32_t total_rows);
@@ -162,13 +163,16 @@ size_t ss_spec_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab
  *   vocab, row_stride   logits rows hold `vocab` entries, `row_stride` elements apart (>= vocab)
  *   logit_dtype         SS_F32 or SS_BF16; rows must start 16-byte aligned
  *   total_rows          host copy of q_indptr[batch]; the draft-side arrays have total_rows-batch entries
+ *   max_q_len           host value: an upper bound of k_b+1 over the batch, or 0 if unknown (SS_OUT_WIDTH is
+ *                       assumed); as for ss_batch.max_q_len a tight bound only saves idle workgroups, and a bound
+ *                       that some request exceeds is a caller error
  *   temperature         device float [batch] (> 0), or NULL to use temperature_scalar for all
  *   ratio_out           device float [total_rows-batch] or NULL: p/q of every draft (diagnostic)
  *   Row statistics are accumulated in fp32/fp64; the resampling pass runs in fp64 so that the
  *   drawn token is reproducible against an fp64 reference.
  */
 int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
-                       const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                       int32_t max_q_len, const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
                        const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
                        const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
                        int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes,
@@ -193,7 +197,7 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
  * sibling, a chain of full-vocabulary passes this library does not implement.
  */
 int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
-                                   int32_t total_rows, const int32_t *q_indptr, const int32_t *tree_parent,
+                                   int32_t total_rows, int32_t max_q_len, const int32_t *q_indptr, const int32_t *tree_parent,
                                    const void *target_logits, const int32_t *draft_tokens, int32_t *accepted_len,
                                    int32_t *out_tokens, int32_t *accepted_nodes, void *workspace,
                                    size_t workspace_bytes, void *stream);

@@ -82,13 +82,13 @@ def lib() -> ctypes.CDLL:
         L.ss_spec_accept_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         L.ss_spec_accept.restype = ctypes.c_int32
         L.ss_spec_accept.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
-                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ss_kv_append.restype = ctypes.c_int32
         L.ss_spec_accept_tree_greedy.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
-                                                 ctypes.c_int32] + [ctypes.c_void_p] * 8 + [ctypes.c_size_t,
+                                                 ctypes.c_int32, ctypes.c_int32] + [ctypes.c_void_p] * 8 + [ctypes.c_size_t,
                                                                                            ctypes.c_void_p]
         L.ss_spec_accept_tree_greedy.restype = ctypes.c_int32
         L.ss_kv_append.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
@@ -280,21 +280,21 @@ def ss_spec_accept_workspace(batch: int, total_rows: int, vocab: int) -> int:
 
 def ss_spec_accept(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,
                    ratio_out: Optional[torch.Tensor], workspace: torch.Tensor, *, greedy: Optional[bool] = None,
-                   per_request_temperature: bool = True) -> None:
+                   per_request_temperature: bool = True, max_q_len: int = 0) -> None:
     g = d["greedy"] if greedy is None else int(greedy)
     temp = d["temperature"] if per_request_temperature else None
     t_scalar = 0.0 if per_request_temperature else float(d["temperature_scalar"])
     _check(lib().ss_spec_accept(d["batch"], d["vocab"], d["row_stride"], _DT[d["logit_dtype"]], d["total_rows"],
-                                _ptr(d["q_indptr"]), _ptr(d["target_logits"]), _ptr(d["draft_logits"]),
+                                max_q_len, _ptr(d["q_indptr"]), _ptr(d["target_logits"]), _ptr(d["draft_logits"]),
                                 _ptr(d["draft_tokens"]), _ptr(d["u_accept"]), _ptr(d["u_sample"]), _ptr(temp),
                                 ctypes.c_float(t_scalar), g, _ptr(accepted_len), _ptr(out_tokens), _ptr(ratio_out),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def ss_spec_accept_tree_greedy(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,
-                               accepted_nodes: torch.Tensor, workspace: torch.Tensor) -> None:
+                               accepted_nodes: torch.Tensor, workspace: torch.Tensor, max_q_len: int = 0) -> None:
     _check(lib().ss_spec_accept_tree_greedy(d["batch"], d["vocab"], d["row_stride"], _DT[d["logit_dtype"]],
-                                            d["total_rows"], _ptr(d["q_indptr"]), _ptr(d["tree_parent"]),
+                                            d["total_rows"], max_q_len, _ptr(d["q_indptr"]), _ptr(d["tree_parent"]),
                                             _ptr(d["target_logits"]), _ptr(d["draft_tokens"]), _ptr(accepted_len),
                                             _ptr(out_tokens), _ptr(accepted_nodes), _ptr(workspace),
                                             workspace.numel() * workspace.element_size(), _stream()))

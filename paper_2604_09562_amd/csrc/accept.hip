@@ -220,7 +220,7 @@ struct ExpTable {
 };
 
 // ---- pass 1 ---------------------------------------------------------------------------------
-// grid: batch * kMaxRows * ceil(nchunks / 4); workgroup (b, j, group): wave wv of it streams chunk
+// grid: batch * rows_max * ceil(nchunks / 4), rows_max from the caller's bound of k+1; workgroup (b, j, group): wave wv of it streams chunk
 // 4 * group + wv of request b's row j (j <= k: target row j; k < j <= 2k: draft row j-k-1; larger j:
 // nothing to do).  A wave owns its chunk alone: all of its 16-byte loads go out first, then the
 // values are folded vector by vector into a per-lane running (max, sum) and reduced across the wave
@@ -249,7 +249,8 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int groups = (w.nchunks + 3) / 4;
     const int chunk = (blockIdx.x % groups) * 4 + wv;
-    const int bj = blockIdx.x / groups, b = bj / kMaxRows, j = bj % kMaxRows;
+    const int rows_max = a.greedy ? a.max_q_len : 2 * a.max_q_len - 1;   // rows a request can have
+    const int bj = blockIdx.x / groups, b = bj / rows_max, j = bj % rows_max;
     const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1;
     if (j > (a.greedy ? k : 2 * k) || chunk >= w.nchunks) return;
     const bool is_draft = j > k;
@@ -836,7 +837,8 @@ static int32_t accept_launch_dt(const AcceptArgs &a, const Workspace &w, unsigne
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
 {
     const Workspace w = carve(a.workspace, a.batch, a.total_rows, a.vocab);
-    const unsigned long long g1 = (unsigned long long)a.batch * kMaxRows * ((w.nchunks + 3) / 4);
+    const unsigned long long g1 =
+        (unsigned long long)a.batch * (a.greedy ? a.max_q_len : 2 * a.max_q_len - 1) * ((w.nchunks + 3) / 4);
     const unsigned long long g2 = (unsigned long long)a.batch * w.nsub;
     if (g1 > 0x7fffffffull || g2 > 0x7fffffffull)
         return fail(SS_ERR_UNSUPPORTED, "batch * vocab too large for one launch");

@@ -113,7 +113,7 @@ size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batc
 {
     if (check_attn_shape(kv, batch, num_q_heads, total_rows) != SS_OK) return 0;
     return attn_workspace_bytes(batch->batch, batch->max_blocks_per_seq, num_q_heads, kv->num_kv_heads, kv->head_dim,
-                                attn_default_waves());
+                                attn_default_waves(), batch->max_q_len ? batch->max_q_len : SS_OUT_WIDTH);
 }
 
 int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,
@@ -132,8 +132,9 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
         return fail(SS_ERR_INVALID_ARG, "k, v, q and out must be 16-byte aligned");
     if (!(sm_scale == sm_scale) || sm_scale <= 0.0f) return fail(SS_ERR_INVALID_ARG, "sm_scale must be positive");
     const int launch_waves = attn_default_waves();
+    const int max_q_len = batch->max_q_len ? batch->max_q_len : SS_OUT_WIDTH;
     const size_t need = attn_workspace_bytes(batch->batch, batch->max_blocks_per_seq, num_q_heads, kv->num_kv_heads,
-                                             kv->head_dim, launch_waves);
+                                             kv->head_dim, launch_waves, max_q_len);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
     if (workspace_bytes < need)
@@ -155,8 +156,8 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.sm_scale = sm_scale;
     a.launch_waves = launch_waves;
     const int G = num_q_heads / kv->num_kv_heads;
-    a.rows_pad = (int)align_up((size_t)SS_OUT_WIDTH * G, 16);
-    a.max_q_len = batch->max_q_len ? batch->max_q_len : SS_OUT_WIDTH;
+    a.rows_pad = (int)align_up((size_t)max_q_len * G, 16);
+    a.max_q_len = max_q_len;
     // carve the workspace
     char *w = static_cast<char *>(workspace);
     a.plan = reinterpret_cast<AttnPlan *>(w);
@@ -199,7 +200,7 @@ size_t ss_spec_accept_workspace(int32_t batch, int32_t total_rows, int32_t vocab
 }
 
 int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
-                                   int32_t total_rows, const int32_t *q_indptr, const int32_t *tree_parent,
+                                   int32_t total_rows, int32_t max_q_len, const int32_t *q_indptr, const int32_t *tree_parent,
                                    const void *target_logits, const int32_t *draft_tokens, int32_t *accepted_len,
                                    int32_t *out_tokens, int32_t *accepted_nodes, void *workspace,
                                    size_t workspace_bytes, void *stream)
@@ -207,6 +208,8 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
     if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
         return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
     if (batch == 0) return SS_OK;
+    if (max_q_len < 0 || max_q_len > SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
     if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
     if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
         return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
@@ -223,7 +226,7 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
-        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, 0,
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, max_q_len,
                                     static_cast<hipStream_t>(stream), "ss_spec_accept_tree_greedy");
         if (rc == SS_OK)
             rc = validate_accept(draft_tokens, nullptr, nullptr, nullptr, batch, total_rows - batch, vocab, 1,
@@ -235,11 +238,12 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
     a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft_tokens = draft_tokens;
     a.accepted_len = accepted_len; a.out_tokens = out_tokens; a.workspace = workspace;
     a.tree_parent = tree_parent; a.accepted_nodes = accepted_nodes;
+    a.max_q_len = max_q_len ? max_q_len : SS_OUT_WIDTH;
     return accept_launch(a, static_cast<hipStream_t>(stream));
 }
 
 int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
-                       const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                       int32_t max_q_len, const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
                        const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
                        const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
                        int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes, void *stream)
@@ -247,6 +251,8 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
         return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
     if (batch == 0) return SS_OK;
+    if (max_q_len < 0 || max_q_len > SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
     if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
     if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
         return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
@@ -267,7 +273,7 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     if (workspace_bytes < need)
         return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     if (g_validate) {
-        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, 0, static_cast<hipStream_t>(stream),
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, max_q_len, static_cast<hipStream_t>(stream),
                                     "ss_spec_accept");
         if (rc == SS_OK)
             rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
@@ -280,6 +286,7 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
     a.draft_tokens = draft_tokens; a.u_accept = u_accept; a.u_sample = u_sample; a.temperature = temperature;
     a.temperature_scalar = temperature_scalar; a.accepted_len = accepted_len; a.out_tokens = out_tokens;
     a.ratio_out = ratio_out; a.workspace = workspace;
+    a.max_q_len = max_q_len ? max_q_len : SS_OUT_WIDTH;
     return accept_launch(a, static_cast<hipStream_t>(stream));
 }
 

@@ -651,10 +651,11 @@ int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, 
 
 }  // namespace
 
-size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves)
+size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves,
+                            int max_q_len)
 {
     const int G = num_q_heads / num_kv_heads;
-    const size_t rows_pad = align_up((size_t)SS_OUT_WIDTH * G, 16);
+    const size_t rows_pad = align_up((size_t)max_q_len * G, 16);
     const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
     size_t n = 256;
     n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);

@@ -62,7 +62,7 @@ struct AttnArgs {
 };
 
 size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim,
-                            int launch_waves);
+                            int launch_waves, int max_q_len);
 bool attn_mfma_supported(const AttnArgs &a);
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 int32_t attn_generic_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
@@ -73,6 +73,7 @@ constexpr int kChunk = 8192;  // vocabulary entries per workgroup in the streami
 
 struct AcceptArgs {
     int32_t batch, vocab, logit_dtype, total_rows, greedy;
+    int32_t max_q_len;   // bound of k_b + 1 over the batch (sizes the row-statistics grid)
     int64_t row_stride;
     const int32_t *q_indptr;
     const void *target, *draft;

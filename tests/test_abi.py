@@ -81,13 +81,15 @@ def test_attention_workspace_query_is_monotone(L):
 
 
 def test_accept_validation(L):
-    def call(batch=4, vocab=1000, stride=1000, dtype=0, rows=12, greedy=0, T=1.0):
-        return L.ss_spec_accept(batch, vocab, stride, dtype, rows, None, None, None, None, None, None, None,
+    def call(batch=4, vocab=1000, stride=1000, dtype=0, rows=12, greedy=0, T=1.0, mq=0):
+        return L.ss_spec_accept(batch, vocab, stride, dtype, rows, mq, None, None, None, None, None, None, None,
                                 ctypes.c_float(T), greedy, None, None, None, None, 0, None)
     assert call(vocab=0) == 1
     assert call(rows=3) == 1 and b"total_rows" in L.ss_last_error()
     assert call(stride=999) == 1 and b"row_stride" in L.ss_last_error()
     assert call(dtype=2) == 1 and b"logit_dtype" in L.ss_last_error()
+    assert call(mq=-1) == 1 and b"max_q_len" in L.ss_last_error()
+    assert call(mq=4) == 1 and b"NULL" in L.ss_last_error()
     assert call() == 1 and b"NULL" in L.ss_last_error()
     assert call(batch=0, rows=0) == 0          # empty batch: no-op
     assert L.ss_spec_accept_workspace(4, 12, 1000) > 0
