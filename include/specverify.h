@@ -54,8 +54,8 @@ typedef enum {
 } ss_dtype;
 
 #define SS_BLOCK_SIZE 16 /* tokens per KV block */
-#define SS_MAX_DEPTH 8   /* largest k; a request brings 1..9 query rows */
-#define SS_OUT_WIDTH 9   /* out_tokens row width = SS_MAX_DEPTH + 1 */
+#define SS_MAX_DEPTH 20  /* largest k (the controller's d_max, Section 3.5); a request brings 1..21 query rows */
+#define SS_OUT_WIDTH 21  /* out_tokens row width = SS_MAX_DEPTH + 1 */
 
 /*
  * Paged KV cache of one layer (Section 2.4).
@@ -84,9 +84,9 @@ typedef struct ss_paged_kv {
  *   kv_len       device int32 [batch]: valid cache positions of each request, INCLUDING the
  *                q_len new tokens of this step, whose K/V the caller has already appended.
  *   q_indptr     device int32 [batch+1]: request b owns query rows q_indptr[b]..q_indptr[b+1]-1
- *                (q_len = k_b + 1 in 1..9, row i = the i-th new token, at position kv_len-q_len+i).
+ *                (q_len = k_b + 1 in 1..SS_OUT_WIDTH, row i = the i-th new token, at position kv_len-q_len+i).
  *   max_q_len    host value: an upper bound of q_len over the batch (the controller's largest depth
- *                this step, plus one), or 0 if unknown (9 is assumed).  A tight bound lets the
+ *                this step, plus one), or 0 if unknown (SS_OUT_WIDTH is assumed).  A tight bound lets the
  *                library pick a kernel with fewer padded query rows; a bound that some request
  *                exceeds is a caller error (rows beyond it are not computed).
  *   tree_mask    NULL: the new tokens of a request form a chain (row i attends new tokens 0..i).
@@ -137,6 +137,10 @@ size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batc
  *
  * Internally the KV stream is cut into partitions that are reduced independently and merged
  * by their log-sum-exp; the result does not depend on the partitioning beyond fp32 rounding.
+ * The matrix-core kernel covers head_dim 128, bf16 queries, bf16 or e4m3 caches, 1/2/4/8 query heads per
+ * KV head and max_q_len * (query heads per KV head) <= 80 query rows per KV head (depth 8 for groups of 8,
+ * depth 19 for groups of 4, any depth for smaller groups); everything else takes a plain fp32 vector
+ * kernel that has no such limits and is several times slower.
  * batch == 0 or total_rows == 0 is a no-op returning SS_OK.
  */
 int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,
@@ -210,7 +214,7 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
  * block_table[b][pos/16], slot pos%16, for every KV head.
  *   kv            the cache to write.  Its k, v (and for SS_FP8_E4M3 k_scale, v_scale) buffers are
  *                 WRITTEN through although the struct declares them const for the read-only calls.
- *   batch         block_table, kv_len, q_indptr as for ss_spec_verify_attn (max_q_len is ignored).
+ *   batch         block_table, kv_len, q_indptr, max_q_len as for ss_spec_verify_attn (tree_mask is not read).
  *   k_new, v_new  device, [total_rows][num_kv_heads][head_dim], dense, new_dtype = SS_F32 or SS_BF16.
  * Stored as: SS_F32 cache the value; SS_BF16 cache nearest bfloat16, ties to even; SS_FP8_E4M3 cache
  * byte = nearest e4m3fn (ties to even) of clamp(x / scale, +-448) with x / scale one float32
@@ -219,7 +223,7 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
  * holds older tokens keeps its scale.  NaN inputs give unspecified NaN payloads.
  * The caller owns all buffers; nothing is allocated; the kernel is enqueued on `stream`.
  * Errors: SS_ERR_INVALID_ARG (NULL pointers, bad dtypes or sizes), SS_ERR_DEVICE (launch failure).
- * Device-side contents (block ids in range, kv_len >= q_len, q_len <= 9) are the caller's contract.
+ * Device-side contents (block ids in range, kv_len >= q_len, q_len <= SS_OUT_WIDTH) are the caller's contract.
  */
 int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k_new, const void *v_new,
                      int32_t new_dtype, int32_t total_rows, void *stream);

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "spec_oracle.c")
 _LIB = os.path.join(_HERE, "libspec_oracle.so")
 _DT = {"f32": 0, "bf16": 1, "fp8": 2}
-OUT_WIDTH = 9  # draft depth is at most 8, so at most 9 tokens come out per request
+OUT_WIDTH = 21  # draft depth is at most 20 (the controller's d_max), so at most 21 tokens come out per request
 
 _lib = None
 

@@ -24,7 +24,7 @@ from typing import List, Tuple
 
 class DepthController:
     def __init__(self, h: int = 10, d_base: float = 5.0, gamma: float = 5.0, d_min: float = 2.0,
-                 d_max: float = 20.0, tau_target: float = 400.0, tau_recent: float = 0.0, k_cap: int = 8):
+                 d_max: float = 20.0, tau_target: float = 400.0, tau_recent: float = 0.0, k_cap: int = 20):
         assert h >= 1
         self.h, self.d_base, self.gamma, self.d_min, self.d_max = h, d_base, gamma, d_min, d_max
         self.tau_target, self.tau_recent, self.k_cap = tau_target, tau_recent, k_cap

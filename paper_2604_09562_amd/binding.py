@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspecverify.so")
 
 SS_F32, SS_BF16, SS_FP8_E4M3 = 0, 1, 2
-SS_OUT_WIDTH = 9
+SS_MAX_DEPTH = 20
+SS_OUT_WIDTH = SS_MAX_DEPTH + 1
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",

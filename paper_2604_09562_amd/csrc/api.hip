@@ -309,6 +309,8 @@ static int32_t check_kv_write(const ss_paged_kv *kv, const ss_batch *batch, int3
         return SS_OK;
     }
     if (batch->max_blocks_per_seq <= 0) return fail(SS_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
+    if (batch->max_q_len < 0 || batch->max_q_len > SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
     if ((int64_t)batch->batch * SS_OUT_WIDTH * kv->num_kv_heads > 0x7fffffffll)
         return fail(SS_ERR_UNSUPPORTED, "batch * kv heads too large for one launch");
     if (!kv->k || !kv->v || !batch->block_table || !batch->kv_len || !batch->q_indptr)
@@ -326,6 +328,7 @@ static KvAppendArgs kv_write_args(const ss_paged_kv *kv, const ss_batch *batch)
     a.num_kv_heads = kv->num_kv_heads; a.head_dim = kv->head_dim; a.kv_dtype = kv->dtype;
     a.batch = batch->batch; a.max_blocks = batch->max_blocks_per_seq;
     a.block_table = batch->block_table; a.kv_len = batch->kv_len; a.q_indptr = batch->q_indptr;
+    a.max_q_len = batch->max_q_len ? batch->max_q_len : SS_OUT_WIDTH;
     return a;
 }
 
@@ -339,7 +342,7 @@ int32_t ss_kv_append(const ss_paged_kv *kv, const ss_batch *batch, const void *k
     if (!k_new || !v_new) return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
     if (g_validate) {
         const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
-                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, batch->max_q_len,
                                           static_cast<hipStream_t>(stream), "ss_kv_append");
         if (rc != SS_OK) return rc;
     }
@@ -357,7 +360,7 @@ int32_t ss_kv_compact(const ss_paged_kv *kv, const ss_batch *batch, const int32_
     if (!accepted_nodes || !accepted_len) return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
     if (g_validate) {
         const int32_t rc = validate_batch(batch->block_table, batch->kv_len, batch->q_indptr, nullptr, batch->batch,
-                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, 0,
+                                          batch->max_blocks_per_seq, kv->num_blocks, total_rows, batch->max_q_len,
                                           static_cast<hipStream_t>(stream), "ss_kv_compact");
         if (rc != SS_OK) return rc;
     }

@@ -40,6 +40,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
 constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
+constexpr int kMaxRowBlocks = 5;     // 16-row blocks one wavefront can keep accumulators for
 constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
 
 // ---------------------------------------------------------------------------------------------
@@ -640,7 +641,7 @@ int32_t launch_nb(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEven
 template <int G>
 int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
-    constexpr int NBMAX = (SS_OUT_WIDTH * G + 15) / 16;
+    constexpr int NBMAX = (SS_OUT_WIDTH * G + 15) / 16 < kMaxRowBlocks ? (SS_OUT_WIDTH * G + 15) / 16 : kMaxRowBlocks;
     const int nb = (a.max_q_len * G + 15) / 16;
     if constexpr (NBMAX >= 5) if (nb == 5) return launch_nb<G, 5>(a, stream, ev0, ev1);
     if constexpr (NBMAX >= 4) if (nb == 4) return launch_nb<G, 4>(a, stream, ev0, ev1);
@@ -670,7 +671,8 @@ bool attn_mfma_supported(const AttnArgs &a)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
     return a.head_dim == D && a.q_dtype == SS_BF16 && (a.kv_dtype == SS_BF16 || a.kv_dtype == SS_FP8_E4M3) &&
-           (G == 1 || G == 2 || G == 4 || G == 8) && a.launch_waves % kWavesPerWg == 0;
+           (G == 1 || G == 2 || G == 4 || G == 8) && a.max_q_len * G <= 16 * kMaxRowBlocks &&
+           a.launch_waves % kWavesPerWg == 0;
 }
 
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)

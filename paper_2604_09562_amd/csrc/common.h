@@ -99,6 +99,7 @@ struct KvAppendArgs {
     const int32_t *block_table, *kv_len, *q_indptr;
     const void *k_new, *v_new;
     int32_t new_dtype;
+    int32_t max_q_len;   // bound of the new tokens per request (sizes the append grid)
 };
 int32_t kv_append_launch(const KvAppendArgs &a, hipStream_t stream);
 int32_t kv_compact_launch(const KvAppendArgs &a, const int32_t *accepted_nodes, const int32_t *accepted_len,

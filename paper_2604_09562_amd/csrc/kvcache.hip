@@ -39,13 +39,13 @@ __device__ __forceinline__ uint8_t to_e4m3_rne(float x, float scale)
     return (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(q, 0.f, 0, false) & 0xffu);
 }
 
-// grid: batch * SS_OUT_WIDTH * kv heads; workgroup = one wavefront
+// grid: batch * max_q_len * kv heads; workgroup = one wavefront
 template <int KV_DT, int NEW_DT, int EPL>
 __global__ __launch_bounds__(64) void kv_append_kernel(KvAppendArgs a)
 {
     const int lane = threadIdx.x;
     const int h = blockIdx.x % a.num_kv_heads;
-    const int bi = blockIdx.x / a.num_kv_heads, i = bi % SS_OUT_WIDTH, b = bi / SS_OUT_WIDTH;
+    const int bi = blockIdx.x / a.num_kv_heads, i = bi % a.max_q_len, b = bi / a.max_q_len;
     const int r0 = a.q_indptr[b], q_len = a.q_indptr[b + 1] - r0;
     if (i >= q_len) return;
     const int D = a.head_dim;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64) void kv_compact_kernel(KvAppendArgs a, const in
 template <int KV_DT, int NEW_DT>
 int32_t launch_append(const KvAppendArgs &a, hipStream_t stream)
 {
-    const unsigned grid = (unsigned)a.batch * SS_OUT_WIDTH * a.num_kv_heads;
+    const unsigned grid = (unsigned)a.batch * a.max_q_len * a.num_kv_heads;
     if (a.head_dim == 128)
         hipLaunchKernelGGL((kv_append_kernel<KV_DT, NEW_DT, 2>), dim3(grid), dim3(64), 0, stream, a);
     else

@@ -32,7 +32,7 @@ import numpy as np
 import torch
 
 BLOCK_SIZE = 16
-KMAX = 8  # largest draft depth a request may carry
+KMAX = 20  # largest draft depth a request may carry (the controller's d_max; the five workloads stay within 8)
 
 _SEED_BASE = 9_562_000
 

@@ -1,0 +1,78 @@
+"""GPU parity at draft depths beyond 8, up to the controller's d_max = 20 (Section 3.5, Eq. 13)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_09562_amd import binding, synth
+from tests.test_gpu_attn import check
+from tests.test_gpu_accept import compare as compare_accept
+from tests.test_gpu_kv import run_and_compare as append_and_compare
+
+pytestmark = pytest.mark.gpu
+
+TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("hq,hkv,kmax,path", [(8, 8, 20, 2), (8, 4, 20, 2), (16, 4, 19, 2), (16, 4, 20, 0), (16, 2, 20, 0)],
+                         ids=["g1", "g2", "g4_mfma", "g4_k20", "g8"])
+def test_attention_up_to_depth_20(oracle, kv_dtype, hq, hkv, kmax, path):
+    # path 2 demands the matrix-core kernel (up to 80 query rows per KV head); beyond that the call
+    # falls back to the vector kernel by itself
+    cfg = LLAMA8B.scaled(batch=7, num_q_heads=hq, num_kv_heads=hkv, kv_dtype=kv_dtype, ctx=("uniform", 30, 900))
+    depth = np.array([kmax, 0, 9, 13, kmax, 8, 17][:7], np.int32)
+    depth = np.minimum(depth, kmax)
+    kv_len = np.array([21, 40, 333, 47, 900, 64, 129], np.int32)
+    for tree in (False, True):
+        inp = synth.make_attention_inputs(cfg, seed=hq + kmax, kv_len=kv_len, depth=depth, tree=tree)
+        binding.ss_set_option("attn_path", path)
+        try:
+            check(inp, oracle, max_q_len=int(depth.max()) + 1, label=f"deep {kv_dtype} {hq}/{hkv} k<={kmax} tree={tree}")
+        finally:
+            binding.ss_set_option("attn_path", 0)
+
+
+def test_matrix_core_kernel_refuses_more_rows_than_it_holds():
+    cfg = LLAMA8B.scaled(batch=2, num_q_heads=16, num_kv_heads=2, ctx=("fixed", (50, 60)), depth=("fixed", 10))
+    inp = synth.make_attention_inputs(cfg, seed=0)
+    d = binding.attention_to_device(inp)
+    out, lse, ws = binding.alloc_attention_outputs(d)
+    binding.ss_set_option("attn_path", 2)
+    try:
+        with pytest.raises(binding.SpecVerifyError):
+            binding.ss_spec_verify_attn(d, out, lse, ws)
+    finally:
+        binding.ss_set_option("attn_path", 0)
+
+
+@pytest.mark.parametrize("greedy", [False, True])
+def test_accept_up_to_depth_20(oracle, greedy):
+    cfg = LLAMA8B.scaled(batch=12, vocab=20011, sigma_draft=("fixed", 0.25))
+    depth = np.array([20, 0, 9, 13, 20, 8, 17, 1, 20, 12, 16, 19], np.int32)
+    inp = synth.make_accept_inputs(cfg, seed=3, depth=depth, greedy=greedy, row_pad=(-20011) % 8)
+    compare_accept(inp, oracle, greedy=greedy, label=f"deep accept greedy={greedy}")
+    assert oracle.spec_accept(inp, greedy=greedy)["accepted_len"].max() > 8, "no request got past depth 8"
+
+
+def test_append_and_tree_steps_up_to_depth_20(oracle):
+    depth = np.array([20, 0, 9, 13, 20, 8, 17, 20], np.int32)
+    kv_len = np.array([21, 40, 333, 47, 900, 64, 129, 60], np.int32)
+    for cfg in (LLAMA8B.scaled(batch=8), FP8_70B.scaled(batch=8)):
+        inp = synth.make_append_inputs(cfg, seed=1, kv_len=kv_len, depth=depth)   # 21 new tokens span three blocks
+        append_and_compare(inp, oracle, f"deep append {cfg.kv_dtype}")
+        # greedy tree acceptance and compaction on the same shapes
+        acc_in = synth.make_tree_accept_inputs(cfg.scaled(vocab=4096), seed=2, depth=depth, hit=0.8)
+        ref = oracle.tree_accept_greedy(acc_in)
+        da = binding.accept_to_device({**acc_in, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
+        n_acc, toks, _, ws = binding.alloc_accept_outputs(da)
+        nodes = torch.full((8, binding.SS_MAX_DEPTH), -77, dtype=torch.int32, device="cuda:0")
+        binding.ss_spec_accept_tree_greedy(da, n_acc, toks, nodes, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(n_acc.cpu().numpy(), ref["accepted_len"]) and np.array_equal(toks.cpu().numpy(), ref["out_tokens"])
+        assert np.array_equal(nodes.cpu().numpy(), ref["accepted_nodes"])
+        d = binding.attention_to_device(inp)
+        binding.ss_kv_compact(d, nodes, n_acc)
+        torch.cuda.synchronize()
+        oracle.kv_compact(inp, ref["accepted_nodes"], ref["accepted_len"])
+        for name in ("k_cache", "v_cache"):
+            assert np.array_equal(d[name].cpu().numpy().view(np.uint8), inp[name].view(np.uint8)), name

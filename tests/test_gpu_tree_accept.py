@@ -13,7 +13,7 @@ TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
 def run_gpu(inp):
     d = binding.accept_to_device({**inp, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
     acc, toks, _, ws = binding.alloc_accept_outputs(d)
-    nodes = torch.full((inp["batch"], 8), -77, dtype=torch.int32, device="cuda:0")
+    nodes = torch.full((inp["batch"], binding.SS_MAX_DEPTH), -77, dtype=torch.int32, device="cuda:0")
     ws.fill_(0xFF)
     binding.ss_spec_accept_tree_greedy(d, acc, toks, nodes, ws)
     torch.cuda.synchronize()
@@ -75,7 +75,7 @@ def test_argument_errors():
     inp = synth.make_tree_accept_inputs(cfg, seed=0)
     d = binding.accept_to_device({**inp, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
     acc, toks, _, ws = binding.alloc_accept_outputs(d)
-    nodes = torch.zeros((2, 8), dtype=torch.int32, device="cuda:0")
+    nodes = torch.zeros((2, binding.SS_MAX_DEPTH), dtype=torch.int32, device="cuda:0")
     with pytest.raises(binding.SpecVerifyError):
         binding.ss_spec_accept_tree_greedy({**d, "tree_parent": None}, acc, toks, nodes, ws)
     with pytest.raises(binding.SpecVerifyError):

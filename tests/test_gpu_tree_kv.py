@@ -51,13 +51,15 @@ def test_compact_fp8_across_every_block_offset(oracle):
 def test_bad_path_rows_touch_nothing_outside_the_new_slots(oracle):
     cfg = LLAMA8B.scaled(batch=3, ctx=("fixed", (40, 50, 60)), depth=("fixed", 4))
     inp = synth.make_attention_inputs(cfg, seed=0, tree=True)
-    nodes = np.array([[3, 2, -1, -1, -1, -1, -1, -1], [7, -1, -1, -1, -1, -1, -1, -1], [2, 4, -1, -1, -1, -1, -1, -1]], np.int32)
+    nodes = np.full((3, binding.SS_MAX_DEPTH), -1, np.int32)
+    nodes[0, :2], nodes[1, :1], nodes[2, :2] = [3, 2], [7], [2, 4]
     n = np.array([2, 1, 2], np.int32)
     d = binding.attention_to_device(inp)
     binding.ss_kv_compact(d, binding._to_dev(nodes, "cuda:0"), binding._to_dev(n, "cuda:0"))
     torch.cuda.synchronize()
     want = dict(inp, k_cache=inp["k_cache"].copy(), v_cache=inp["v_cache"].copy())
-    good = np.array([[3, -1, -1, -1, -1, -1, -1, -1], [-1] * 8, [2, 4, -1, -1, -1, -1, -1, -1]], np.int32)
+    good = np.full((3, binding.SS_MAX_DEPTH), -1, np.int32)
+    good[0, :1], good[2, :2] = [3], [2, 4]
     oracle.kv_compact(want, good, np.array([1, 0, 2], np.int32))   # moves up to the offending entry only
     for name in ("k_cache", "v_cache"):
         assert np.array_equal(d[name].cpu().numpy().view(np.uint8), want[name].view(np.uint8))
@@ -92,7 +94,7 @@ def test_four_tree_steps(oracle, base_cfg):
         binding.ss_spec_verify_attn(d, out, lse, ws, max_q_len=mq)
         da = binding.accept_to_device({**acc_in, "draft_logits": None, "u_accept": None, "u_sample": None, "temperature": None})
         n_acc, toks, _, ws_a = binding.alloc_accept_outputs(da)
-        nodes = torch.full((B, 8), -77, dtype=torch.int32, device="cuda:0")
+        nodes = torch.full((B, binding.SS_MAX_DEPTH), -77, dtype=torch.int32, device="cuda:0")
         binding.ss_spec_accept_tree_greedy(da, n_acc, toks, nodes, ws_a)
         binding.ss_kv_compact(d, nodes, n_acc)
         binding.ss_kv_commit(d["q_indptr"], n_acc, d["kv_len"])

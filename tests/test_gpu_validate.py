@@ -49,7 +49,7 @@ def test_valid_batch_passes_and_results_do_not_change(validating):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("what", ["block_id_high", "block_id_negative", "kv_len_short", "kv_len_long", "q_len_10",
+@pytest.mark.parametrize("what", ["block_id_high", "block_id_negative", "kv_len_short", "kv_len_long", "q_len_22",
                                   "q_start", "q_total"])
 def test_bad_attention_metadata_is_reported(validating, what):
     inp = attn_case()
@@ -62,8 +62,8 @@ def test_bad_attention_metadata_is_reported(validating, what):
         inp["kv_len"][b] = int(inp["depth"][b])          # fewer cache positions than query rows
     elif what == "kv_len_long":
         inp["kv_len"][b] = inp["max_blocks_per_seq"] * 16 + 1
-    elif what == "q_len_10":
-        inp["q_indptr"][b + 1:] += 10 - (inp["q_indptr"][b + 1] - inp["q_indptr"][b])
+    elif what == "q_len_22":
+        inp["q_indptr"][b + 1:] += 22 - (inp["q_indptr"][b + 1] - inp["q_indptr"][b])
         inp["total_rows"] = int(inp["q_indptr"][-1])
         R = inp["total_rows"]
         inp["q"] = np.zeros((R,) + inp["q"].shape[1:], dtype=inp["q"].dtype)

@@ -16,7 +16,7 @@ from paper_2604_09562_amd import synth
 from tests.helpers import softmax64
 
 TINY = synth.CONFIGS[0]
-W = 9
+W = 21   # row width of out_tokens: the largest draft depth plus one
 
 
 def _batch(tgt_rows, drf_rows, tokens, u_acc, u_s, depths, T=1.0, greedy=0, dtype="f32"):
@@ -41,8 +41,8 @@ def _batch(tgt_rows, drf_rows, tokens, u_acc, u_s, depths, T=1.0, greedy=0, dtyp
 
 # ----------------------------------------------------------------------------- greedy
 def test_greedy_is_longest_prefix_matching_target_argmax(oracle):
-    cfg = TINY.scaled(batch=64, vocab=50, depth=("uniform", 0, 8), sigma_draft=("fixed", 0.3),
-                      logit_dtype="bf16")   # bf16 + small vocab: argmax ties do occur
+    cfg = TINY.scaled(batch=64, vocab=50, depth=("uniform", 0, 20), sigma_draft=("fixed", 0.3),
+                      logit_dtype="bf16")   # bf16 + small vocab: argmax ties do occur; depths up to the largest allowed
     inp = synth.make_accept_inputs(cfg, seed=0, greedy=True)
     res = oracle.spec_accept(inp)
     tgt = synth.decode_storage(inp["target_logits"], "bf16")

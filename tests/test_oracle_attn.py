@@ -69,7 +69,7 @@ def test_decoders_match_torch_conversions(oracle):
     assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
 
 
-@pytest.mark.parametrize("depth", [0, 1, 4, 8])
+@pytest.mark.parametrize("depth", [0, 1, 4, 8, 20])
 @pytest.mark.parametrize("kv_dtype,q_dtype", [("f32", "f32"), ("bf16", "bf16"), ("fp8", "bf16")])
 def test_matches_library_attention(oracle, depth, kv_dtype, q_dtype):
     # depth 0 is ordinary single-token decode attention over kv_len keys

@@ -40,9 +40,9 @@ def test_factor_saturation_and_clipping():
         c = DepthController(d_max=1e9)
         d, *_ = c.update(1.0, 0.0, t)
         assert d == pytest.approx(5.0 + 0.5 * scale)
-    c = DepthController()                      # unclipped 5 + 0.5*400 = 205 -> d_max = 20, b_micro = 4, k capped at 8
+    c = DepthController()                      # unclipped 5 + 0.5*400 = 205 -> d_max = 20, b_micro = 4, k = 20
     d, b, _, k = c.update(1.0, 0.0, 0.0)
-    assert (d, b, k) == (20.0, 4, 8)
+    assert (d, b, k) == (20.0, 4, 20)
     c = DepthController(d_base=0.5)            # below d_min
     d, b, _, k = c.update(0.0, 0.0, 400.0)
     assert (d, b, k) == (2.0, 40, 2)

@@ -12,13 +12,14 @@ from paper_2604_09562_amd import synth
 from tests.helpers import gather_kv
 
 TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
+NODES = 20   # row width of accepted_nodes: the largest draft depth
 
 
 def random_paths(inp, seed):
     """A random root path of every request's tree: (accepted_nodes [B][8], accepted_len [B])."""
     rng = np.random.default_rng(seed)
     B = inp["batch"]
-    nodes = np.full((B, 8), -1, np.int32)
+    nodes = np.full((B, NODES), -1, np.int32)
     n = np.zeros(B, np.int32)
     for b in range(B):
         r0, q_len = int(inp["q_indptr"][b]), int(inp["q_indptr"][b + 1] - inp["q_indptr"][b])
@@ -103,7 +104,7 @@ def test_a_chain_path_moves_nothing(oracle):
     cfg = LLAMA8B.scaled(batch=6, num_q_heads=8, num_kv_heads=2, ctx=("uniform", 9, 80), depth=("uniform", 0, 8))
     pre = synth.make_attention_inputs(cfg, seed=1, tree=True)
     n = (pre["depth"] // 2).astype(np.int32)
-    nodes = np.full((6, 8), -1, np.int32)
+    nodes = np.full((6, NODES), -1, np.int32)
     for b in range(6):
         nodes[b, :n[b]] = np.arange(1, n[b] + 1)
     post = copy_batch(pre)
@@ -135,9 +136,9 @@ def test_bad_paths_rejected(oracle):
     cfg = LLAMA8B.scaled(batch=2, num_q_heads=8, num_kv_heads=2, ctx=("fixed", (40, 50)), depth=("fixed", 4))
     pre = synth.make_attention_inputs(cfg, seed=0, tree=True)
     for path, n in (([2, 1], 2), ([5], 1), ([1, 1], 2), ([0], 1)):
-        nodes = np.full((2, 8), -1, np.int32)
+        nodes = np.full((2, NODES), -1, np.int32)
         nodes[1, :len(path)] = path
         with pytest.raises(ValueError):
             oracle.kv_compact(copy_batch(pre), nodes, np.array([0, n], np.int32))
     with pytest.raises(ValueError):
-        oracle.kv_compact(copy_batch(pre), np.full((2, 8), -1, np.int32), np.array([0, 5], np.int32))
+        oracle.kv_compact(copy_batch(pre), np.full((2, NODES), -1, np.int32), np.array([0, 5], np.int32))

@@ -32,8 +32,8 @@ def test_hand_worked_tree(oracle):
     # node4 right (1), node5 = 4 (the tied maximum's higher index: not the argmax), node6 wrong (1, needs 0)
     r = oracle.tree_accept_greedy(_explicit(rows, parent, [2, 3, 3, 1, 4, 1]))
     assert r["accepted_len"][0] == 2
-    assert r["accepted_nodes"][0].tolist() == [2, 4, -1, -1, -1, -1, -1, -1]
-    assert r["out_tokens"][0].tolist() == [3, 1, 0, -1, -1, -1, -1, -1, -1]
+    assert r["accepted_nodes"][0].tolist() == [2, 4] + [-1] * 18
+    assert r["out_tokens"][0].tolist() == [3, 1, 0] + [-1] * 18
     # make node 6 right as well: the walk reaches a leaf and emits the leaf row's argmax as the bonus token
     r = oracle.tree_accept_greedy(_explicit(rows, parent, [2, 3, 3, 1, 4, 0]))
     assert r["accepted_len"][0] == 3
@@ -55,7 +55,7 @@ def test_chain_trees_equal_the_chain_walk(oracle):
     assert np.array_equal(got["accepted_len"], ref["accepted_len"])
     assert np.array_equal(got["out_tokens"], ref["out_tokens"])
     for b, n in enumerate(got["accepted_len"]):
-        assert got["accepted_nodes"][b].tolist() == list(range(1, n + 1)) + [-1] * (8 - n)
+        assert got["accepted_nodes"][b].tolist() == list(range(1, n + 1)) + [-1] * (20 - n)
 
 
 @pytest.mark.parametrize("logit_dtype", ["f32", "bf16"])
