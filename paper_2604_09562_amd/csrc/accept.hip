@@ -372,6 +372,19 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
     const double inv_t = a.greedy ? 1.0 : 1.0 / (double)T;
     const int nrows = a.greedy ? k + 1 : 2 * k + 1;
 
+    // Wave 0's gathers (draft token, then its two logits) depend on nothing the row merge below
+    // produces: they are requested first so that their latency runs under it.
+    int x_early = -1;
+    float lp_early = 0.f, lq_early = 0.f, u_early = 0.f;
+    if (wave == 0 && lane < k && !a.tree_parent) {
+        x_early = a.draft_tokens[d0 + lane];
+        if (!a.greedy) {
+            lp_early = load_logit(a.target, t0 + lane, a.row_stride, a.logit_dtype, x_early);
+            lq_early = load_logit(a.draft, d0 + lane, a.row_stride, a.logit_dtype, x_early);
+            u_early = a.u_accept[d0 + lane];
+        }
+    }
+
     for (int j = wave; j < nrows; j += 4) {
         const int64_t ry = j <= k ? (int64_t)t0 + j : (int64_t)a.total_rows + d0 + (j - k - 1);
         float m = -INFINITY;
@@ -429,17 +442,16 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
     bool reject = false;
     int x = -1;
     if (lane < k) {
-        x = a.draft_tokens[d0 + lane];
+        x = x_early;
         if (a.greedy) {
             reject = row_arg[lane] != x;
         } else {
-            const double lp = load_logit(a.target, t0 + lane, a.row_stride, a.logit_dtype, x);
-            const double lq = load_logit(a.draft, d0 + lane, a.row_stride, a.logit_dtype, x);
+            const double lp = lp_early, lq = lq_early;
             // p(x)/q(x) = exp((lp-mp)/T - (lq-mq)/T) * Zq/Zp
             const double e = (lp - (double)row_m[lane]) * inv_t - (lq - (double)row_m[k + 1 + lane]) * inv_t;
             const double rho = exp(e) * (row_z[k + 1 + lane] / row_z[lane]);
             if (a.ratio_out) a.ratio_out[d0 + lane] = (float)rho;
-            reject = !((double)a.u_accept[d0 + lane] < rho);
+            reject = !((double)u_early < rho);
         }
     }
     const unsigned long long rej = __ballot(reject);
@@ -619,6 +631,8 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     const double zq0 = own && pk.q_row >= 0 ? w.zq[ob + tid] : 0.0;
     const double pp0 = own && pk.q_row >= 0 ? w.pp[ob + tid] : 0.0;
     const double qq0 = own && pk.q_row >= 0 ? w.qq[ob + tid] : 0.0;
+    const int cnt0 = own && pk.q_row >= 0 ? w.blk_cnt[ob + tid] : 0;       // this lane's block: its listed run
+    const int base0 = own && pk.q_row >= 0 ? w.blk_base[ob + tid] : 0;
     ex.init();
 
     // exact normalisers, then the mass of every block
@@ -646,9 +660,9 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
             // The listed boundary entries, now that Zp and Zq are exact: lane c adds block c's run in its stored order.
             __syncthreads();
             for (int c = tid; c < w.nsub; c += kThreads) {
-                const int cnt = w.blk_cnt[ob + c];
+                const int cnt = c == tid ? cnt0 : w.blk_cnt[ob + c];
                 if (cnt > 0) {
-                    const int64_t l0 = (int64_t)b * kAmbCap + w.blk_base[ob + c];
+                    const int64_t l0 = (int64_t)b * kAmbCap + (c == tid ? base0 : w.blk_base[ob + c]);
                     double add = 0.0;
                     for (int e = 0; e < cnt; ++e) {
                         const double r = w.amb_ep[l0 + e] * inv_zp - w.amb_eq[l0 + e] * inv_zq;
