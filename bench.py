@@ -203,7 +203,7 @@ def main() -> int:
     t_app, t_com = [], []
     for i in range(8):
         ev[0].record()
-        binding.ss_kv_append(d_app)
+        binding.ss_kv_append(d_app, max_q_len=max_q_len)
         ev[1].record()
         binding.ss_kv_commit(d_att[0]["q_indptr"], n_acc, lens)
         ev[2].record()

@@ -228,16 +228,17 @@ def alloc_attention_outputs(d: Dict[str, object], device="cuda:0", max_q_len: in
     return out, lse, ws
 
 
-def ss_kv_append(d: Dict[str, object]) -> None:
+def ss_kv_append(d: Dict[str, object], max_q_len: int = 0) -> None:
     """Enqueue the append of `k_new`/`v_new` into the device batch's paged cache (written in place)."""
-    kv, bt = _descriptors(d, 0)
+    kv, bt = _descriptors(d, max_q_len)
     _check(lib().ss_kv_append(ctypes.byref(kv), ctypes.byref(bt), _ptr(d["k_new"]), _ptr(d["v_new"]),
                               _DT[d["new_dtype"]], d["total_rows"], _stream()))
 
 
-def ss_kv_compact(d: Dict[str, object], accepted_nodes: torch.Tensor, accepted_len: torch.Tensor) -> None:
+def ss_kv_compact(d: Dict[str, object], accepted_nodes: torch.Tensor, accepted_len: torch.Tensor,
+                  max_q_len: int = 0) -> None:
     """Enqueue the move of every request's accepted tree path to the slots a chain would occupy (cache in place)."""
-    kv, bt = _descriptors(d, 0)
+    kv, bt = _descriptors(d, max_q_len)
     _check(lib().ss_kv_compact(ctypes.byref(kv), ctypes.byref(bt), _ptr(accepted_nodes), _ptr(accepted_len),
                                d["total_rows"], _stream()))
 
