@@ -1,6 +1,11 @@
-"""Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+"""Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU).
+
+Every source is compiled to an object of its own, several at a time, then linked; the objects live
+in ``_build/`` next to this file.
+"""
 from __future__ import annotations
 
+import concurrent.futures
 import os
 import subprocess
 import sys
@@ -8,28 +13,41 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["api.hip", "attn_mfma.hip", "attn_generic.hip", "accept.hip", "kvcache.hip", "validate.hip", "depth_controller.cpp", "router.cpp"]
+# the per-grouping attention units take longest: start them first
+SOURCES = ["attn_mfma_g8.hip", "attn_mfma_g4.hip", "attn_mfma_g2.hip", "attn_mfma_g1.hip", "accept.hip", "api.hip",
+           "attn_mfma.hip", "attn_generic.hip", "kvcache.hip", "validate.hip", "depth_controller.cpp", "router.cpp"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# the host pass reports that it does not know the packed-fp32 feature; that line is noise
+NOISE = "is not a recognized feature for this target"
 
 
-def build(verbose: bool = False) -> str:
-    cmd = [
-        "hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
-        "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        "-o", LIB,
-    ] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    # the host pass reports that it does not know the packed-fp32 feature; that line is noise
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    err = "\n".join(l for l in res.stderr.splitlines() if NOISE not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + err)
+    return err
+
+
+def build(verbose: bool = False, jobs: int = 0) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(len(SOURCES), max(1, (os.cpu_count() or 2) - 1), 8)
+    objects = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+        futs = [pool.submit(_run, ["hipcc", *FLAGS, "-c", os.path.join(CSRC, s), "-o", o], verbose)
+                for s, o in zip(SOURCES, objects)]
+        warnings = [f.result() for f in futs]   # raises the first failure
+    warnings.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objects], verbose))
+    if verbose:
+        for w in warnings:
+            if w.strip():
+                print(w, file=sys.stderr)
     return LIB
 
 

@@ -20,28 +20,10 @@
 // holds 8 consecutive d of one token; for V a lane holds d = 8*i .. 8*i+7 of four tokens and
 // the eight M-blocks of O^T are the eight interleaved d-phases, so no transpose through LDS is
 // needed (only a 16-bit pack per operand register).
-#include <type_traits>
-
-#include <hip/hip_ext.h>
-
 #include "common.h"
 
 namespace ss {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef float float2v __attribute__((ext_vector_type(2)));
-
-constexpr int D = 128;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
-constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
-constexpr int kMaxRowBlocks = 5;     // 16-row blocks one wavefront can keep accumulators for
-constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
 
 // ---------------------------------------------------------------------------------------------
 // plan: workgroup (b, g) sums the tile counts of the requests in front of b, writes the flat tile
@@ -126,530 +108,6 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// streaming kernel
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t pack_hi16(uint32_t lo_src, uint32_t hi_src)
-{
-    // (hi_src & 0xffff0000) | (lo_src >> 16): upper halves of two words
-    return __builtin_amdgcn_perm(hi_src, lo_src, 0x07060302u);
-}
-__device__ __forceinline__ uint32_t pack_lo16(uint32_t lo_src, uint32_t hi_src)
-{
-    return __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);
-}
-
-// 8 e4m3 bytes (two words) -> 8 bf16 (exact: e4m3 has 4 significant bits)
-__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1)
-{
-    const float2v a = __builtin_amdgcn_cvt_pk_f32_fp8(w0, false);
-    const float2v b = __builtin_amdgcn_cvt_pk_f32_fp8(w0, true);
-    const float2v c = __builtin_amdgcn_cvt_pk_f32_fp8(w1, false);
-    const float2v d = __builtin_amdgcn_cvt_pk_f32_fp8(w1, true);
-    uint4 r;
-    r.x = pack_hi16(__float_as_uint(a.x), __float_as_uint(a.y));
-    r.y = pack_hi16(__float_as_uint(b.x), __float_as_uint(b.y));
-    r.z = pack_hi16(__float_as_uint(c.x), __float_as_uint(c.y));
-    r.w = pack_hi16(__float_as_uint(d.x), __float_as_uint(d.y));
-    return r;
-}
-
-template <bool FP8>
-struct TileRegs {
-    // bf16: k[ks] = 8 bf16 of token (lane&15) at d = 32*ks + 8*(lane>>4)
-    // fp8 : k[kk] = 16 bytes of token (lane&15) at d = 64*kk + 16*(lane>>4)   (kk = 0,1)
-    uint4 k[FP8 ? 2 : 4];
-    // bf16: v[e] = 8 bf16 of token 4*(lane>>4)+e at d = 8*(lane&15)
-    // fp8 : v[e] = 8 bytes of the same
-    typename std::conditional<FP8, uint2, uint4>::type v[4];
-    float ks, vs;  // block scales (fp8), 1 otherwise
-};
-
-// All loads of one tile are vector loads issued back to back, so one counter orders them and the
-// consumer can wait for exactly this tile.  `addr` = physical block * kv heads + kv head indexes
-// both the 4 KB (2 KB for e4m3) tile and its scale.  `vzero` is a lane register holding 0 that the
-// compiler cannot see through: it keeps the (wave-uniform) scale reads on the vector path too.
-template <bool FP8>
-__device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, const float *__restrict__ k_scale,
-                                          const float *__restrict__ v_scale, int addr, int lane, int vzero)
-{
-    constexpr int ES = FP8 ? 1 : 2;
-    const int64_t blk = (int64_t)addr * (kTile * D * ES);
-    const char *kp = static_cast<const char *>(a.k) + blk + (lane & 15) * (D * ES) + (lane >> 4) * 16;
-    const char *vp = static_cast<const char *>(a.v) + blk + (lane >> 4) * (4 * D * ES) + (lane & 15) * (8 * ES);
-#pragma unroll
-    for (int i = 0; i < (FP8 ? 2 : 4); ++i) t.k[i] = *reinterpret_cast<const uint4 *>(kp + i * 64);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if constexpr (FP8)
-            t.v[e] = *reinterpret_cast<const uint2 *>(vp + e * (D * ES));
-        else
-            t.v[e] = *reinterpret_cast<const uint4 *>(vp + e * (D * ES));
-    }
-    if constexpr (FP8) {
-        t.ks = k_scale[addr + vzero];
-        t.vs = v_scale[addr + vzero];
-    } else {
-        t.ks = 1.f;
-        t.vs = 1.f;
-    }
-}
-
-// NB    16-row blocks of query rows the kernel is compiled for (covers max_q_len * G rows)
-// NBUF  KV tiles resident per wave: one being consumed, NBUF-1 in flight from HBM
-// QLDS  keep the query operands in LDS (in operand order, one 1 KB line per row block and k-step)
-//       instead of registers: for many row blocks the registers are needed for the accumulators
-// TREE  the new tokens of a request form a draft tree: a row's visibility among them comes from its
-//       mask word instead of the chain's "tokens up to my own"
-template <int G, int NB, bool FP8, int NBUF, bool QLDS, bool TREE>
-__global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
-    AttnArgs a, const int32_t *__restrict__ tile_addr, const int32_t *__restrict__ wave_desc,
-    const int32_t *__restrict__ tile_prefix,
-    const int32_t *__restrict__ kv_len, const int32_t *__restrict__ q_indptr, const float *__restrict__ k_scale,
-    const float *__restrict__ v_scale)
-{
-    // The metadata arrays come in as separate no-alias arguments so that their wave-uniform reads
-    // become scalar loads (own counter, no ordering against the vector KV loads).
-    __shared__ int32_t id_lds[kWavesPerWg][kIdWindow];
-    __shared__ uint4 q_lds[QLDS ? kWavesPerWg * NB * 4 * 64 : 1];
-    const int lane = threadIdx.x & 63;
-    const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wave = blockIdx.x * kWavesPerWg + wslot;
-    const int r16 = lane & 15, jq = lane >> 4;
-    int vzero;
-    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
-    int32_t *ids = id_lds[wslot];
-    uint4 *qs = q_lds + (QLDS ? wslot * NB * 4 * 64 : 0) + (QLDS ? lane : 0);
-
-    // where this wave's span starts: written by the plan kernel (waves past the partition count get x0 == x1)
-    int b, g, tile, nb_tiles;
-    long long x0, x1;
-    int meta_L, meta_q0, meta_q1, meta_nbt;   // kv_len / q_indptr / tile count of the next unit to open
-    int desc_addr[kDescAddrs];
-    {
-        const int32_t *d = wave_desc + (long long)wave * kDescInts;
-        b = d[0]; g = d[1]; tile = d[2]; nb_tiles = d[3];
-        x0 = d[4]; x1 = d[5];
-        meta_L = d[6]; meta_q0 = d[7]; meta_q1 = d[8]; meta_nbt = nb_tiles;
-#pragma unroll
-        for (int j = 0; j < kDescAddrs; ++j) desc_addr[j] = d[9 + j];
-    }
-    static_assert(NBUF - 1 <= kDescAddrs, "descriptor carries too few tile addresses");
-    if (x0 >= x1) return;
-
-    // ---- state of the unit being computed ----
-    int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
-    int seg_left = 0;                 // of those, tiles that still belong to the current unit
-    int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has (for its partial)
-    bf16x8 qreg[QLDS ? 1 : NB][4];    // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
-    int lim[TREE ? 1 : NB];           // chain: last visible cache position of this lane's row in block nb
-    uint32_t newmask[TREE ? NB : 1];  // tree: which new tokens of the request the lane's row attends
-    int ctx = 0;                      // cache positions before the unit's new tokens
-    float m_run[NB], l_run[NB];
-    float4v acc[8][NB];
-    const float sc2 = a.sm_scale * kLog2e;
-
-    // (the metadata of the unit after the current one is fetched a unit ahead)
-    auto begin_unit_issue = [&]() {
-        L = meta_L;
-        q0 = meta_q0;
-        q_len = meta_q1 - meta_q0;
-        nb_tiles = meta_nbt;
-        rows = q_len * G;
-        nbu = (rows + 15) >> 4;
-        ctx = L - q_len;
-        {
-            const int nb_ = (g + 1 == a.num_kv_heads) ? b + 1 : b;   // request of the next unit
-            if (nb_ != b && nb_ < a.batch) {
-                meta_L = kv_len[nb_];
-                meta_q0 = q_indptr[nb_];
-                meta_q1 = q_indptr[nb_ + 1];
-                meta_nbt = tile_prefix[nb_ + 1] - tile_prefix[nb_];
-            }
-        }
-        seg_left = nb_tiles - tile < span_left ? nb_tiles - tile : span_left;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int n = nb * 16 + r16;
-            const bool ok = n < rows;
-            const int qi = n / G, hh = n % G;
-            if constexpr (TREE)   // padding rows see every new token: harmless, and no row is empty
-                newmask[nb] = ok ? a.tree_mask[q0 + qi] : (2u << (q_len - 1)) - 1u;
-            else
-                lim[nb] = ok ? L - q_len + qi : L - 1;
-            const char *qp = static_cast<const char *>(a.q) +
-                             (((long long)(q0 + qi) * a.num_q_heads + g * G + hh) * D) * 2;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const int d0 = FP8 ? ((ks >> 1) * 64 + jq * 16 + (ks & 1) * 8) : (ks * 32 + jq * 8);
-                uint4 w = make_uint4(0, 0, 0, 0);
-                if (ok) w = *reinterpret_cast<const uint4 *>(qp + d0 * 2);
-                if constexpr (QLDS)
-                    qs[(nb * 4 + ks) * 64] = w;
-                else
-                    qreg[nb][ks] = __builtin_bit_cast(bf16x8, w);
-            }
-            m_run[nb] = kNoMax;
-            l_run[nb] = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-    // Have the queries arrive here, inside the rarely taken branch, so that the steady-state path
-    // never carries a pending load of them.
-    auto begin_unit_wait = [&]() {
-        if constexpr (!QLDS) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
-        }
-        if constexpr (TREE) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(newmask[nb]));
-        }
-    };
-
-    auto end_unit = [&]() {
-        // The accumulators were last written by MFMAs in another basic block: give them the wait
-        // states a read needs before anything below touches them.
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-        const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
-        float *po = a.part_o + slot * a.rows_pad * D;
-        float *pml = a.part_ml + slot * a.rows_pad * 2;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if (nb < nbu) {
-                float l = l_run[nb];
-                l += __shfl_xor(l, 16);
-                l += __shfl_xor(l, 32);
-                const int n = nb * 16 + r16;
-                if (n < rows) {
-                    if (jq == 0) {
-                        pml[n * 2 + 0] = m_run[nb];
-                        pml[n * 2 + 1] = l;
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        // accumulator row 4*jq+e of M-block mb is d = 8*(4*jq+e) + mb
-                        float *dst = po + n * D + (jq * 4 + e) * 8;
-                        float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
-                        float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
-                        *reinterpret_cast<float4v *>(dst) = lo;
-                        *reinterpret_cast<float4v *>(dst + 4) = hi;
-                    }
-                }
-            }
-        }
-        // next unit (its metadata is already in meta_*)
-        tile = 0;
-        if (++g == a.num_kv_heads) {
-            g = 0;
-            ++b;
-        }
-    };
-
-    // One tile: S^T = K Q^T for all row blocks, softmax, O^T += V^T P^T.  Row blocks beyond the
-    // unit's rows hold zero queries; they are computed anyway (cheaper than branching, which was
-    // measured) and never stored.  Straight-line code apart from the rare rescale: masks are selects
-    // that are all-pass on ordinary tiles.  (No branch may sit between an MFMA and the first read of
-    // its result: the wait states the hardware needs there are only inserted inside a block.)
-    // The order of the pieces is chosen so that vector work that does not depend on a matrix result
-    // follows each group of MFMAs: the V operands are built while S^T is in the matrix pipeline, and
-    // a row block's exponentials while the previous block's output MFMAs run.
-    auto compute = [&](const TileRegs<FP8> &t, int ti) {
-        const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
-
-        bf16x8 kop[4];
-        if constexpr (FP8) {
-            kop[0] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].x, t.k[0].y));
-            kop[1] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[0].z, t.k[0].w));
-            kop[2] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].x, t.k[1].y));
-            kop[3] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(t.k[1].z, t.k[1].w));
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kop[ks] = __builtin_bit_cast(bf16x8, t.k[ks]);
-        }
-        float4v s[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) s[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-        if constexpr (QLDS) {
-            // operands come from LDS a few MFMAs ahead of their use, so that its latency is covered
-            constexpr int NOPS = 4 * NB, AHEAD = NOPS < 6 ? NOPS : 6;
-            uint4 qb[AHEAD];
-#pragma unroll
-            for (int i = 0; i < AHEAD; ++i) qb[i] = qs[((i % NB) * 4 + i / NB) * 64];
-#pragma unroll
-            for (int i = 0; i < NOPS; ++i) {
-                const int ks = i / NB, nb = i % NB;
-                const bf16x8 qop = __builtin_bit_cast(bf16x8, qb[i % AHEAD]);
-                if (i + AHEAD < NOPS) {
-                    const int i2 = i + AHEAD;
-                    qb[i % AHEAD] = qs[((i2 % NB) * 4 + i2 / NB) * 64];
-                }
-                s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qop, s[nb], 0, 0, 0);
-            }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
-        }
-
-        // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
-        // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
-        const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
-        const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
-        short4v vop[8];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {   // word h of each token's 8 values holds d-phases 2h and 2h+1
-            uint32_t w[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if constexpr (FP8) {
-                    const uint32_t src = (h < 2) ? t.v[e].x : t.v[e].y;   // two e4m3 bytes -> two bf16, exact
-                    const float2v f = (h & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true)
-                                              : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
-                    w[e] = pack_hi16(__float_as_uint(f.x), __float_as_uint(f.y));
-                } else {
-                    w[e] = (&t.v[e].x)[h];
-                }
-            }
-            uint2 lo, hi;
-            lo.x = pack_lo16(w[0], w[1]) & m01;
-            lo.y = pack_lo16(w[2], w[3]) & m23;
-            hi.x = pack_hi16(w[0], w[1]) & m01;
-            hi.y = pack_hi16(w[2], w[3]) & m23;
-            vop[2 * h] = __builtin_bit_cast(short4v, lo);
-            vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
-        }
-
-        // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
-        // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
-        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
-        const float kscale = sc2 * t.ks;
-        float sv[NB][4];
-        bool trig = false;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if constexpr (TREE) {
-                // A 64-position window: 32 positions of old context (all visible) below the 32 mask
-                // bits of the new tokens; shifted so that bit e is this lane's position tok0 + e.
-                // Positions past the cache end are past the mask's last set bit.
-                const int sh = tok0 - ctx + 32;
-                const uint64_t window = ((uint64_t)newmask[nb] << 32) | 0xffffffffull;
-                const uint32_t vis = sh < 0 ? 0xfu : (uint32_t)(window >> (sh & 63));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? s[nb][e] * kscale : -INFINITY;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                    sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
-            }
-            const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-            trig |= lane_mx > m_run[nb] + kSlack;
-        }
-        if (__any(trig)) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[nb], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-                l_run[nb] *= alpha;
-#pragma unroll
-                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
-                m_run[nb] = m_new;
-            }
-        }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
-            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
-            uint2 pk;
-            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-            const short4v pop = __builtin_bit_cast(short4v, pk);
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
-        }
-    };
-
-    // one step of the compute side: consume a tile; at the end of a unit segment write its partial
-    // and open the next segment (its query loads go out ahead of the next KV prefetch)
-    auto step = [&](const TileRegs<FP8> &t) {
-        compute(t, tile);
-        ++tile;
-        --span_left;
-        if (--seg_left == 0) {
-            end_unit();
-            if (span_left > 0) {
-                begin_unit_issue();
-                begin_unit_wait();
-            }
-        }
-    };
-
-    // ---- load side: a linear walk over the span's tile addresses, staged in LDS a window at a time ----
-    bool first_window = true;
-    for (long long c0 = x0; c0 < x1; c0 += kIdWindow) {
-        const int n = (int)(x1 - c0 < kIdWindow ? x1 - c0 : kIdWindow);
-        // the window's addresses: vector reads now, into LDS once they have arrived
-        int idtmp[kIdWindow / 64];
-#pragma unroll
-        for (int i = 0; i < kIdWindow / 64; ++i) idtmp[i] = (i * 64 + lane < n) ? tile_addr[c0 + i * 64 + lane] : 0;
-        // the first NBUF-1 tiles do not wait for that: their addresses come by scalar reads
-        int first_addr[NBUF - 1];
-#pragma unroll
-        for (int j = 0; j < NBUF - 1; ++j)
-            first_addr[j] = first_window ? desc_addr[j] : tile_addr[c0 + (j < n ? j : n - 1)];
-        if (first_window) begin_unit_issue();   // queries of the first unit go out before any KV tile
-
-        TileRegs<FP8> buf[NBUF];
-#pragma unroll
-        for (int j = 0; j < NBUF - 1; ++j)
-            if (j < n) load_tile<FP8>(buf[j], a, k_scale, v_scale, first_addr[j], lane, vzero);
-        if (first_window) begin_unit_wait();
-        first_window = false;
-#pragma unroll
-        for (int i = 0; i < kIdWindow / 64; ++i) ids[i * 64 + lane] = idtmp[i];
-
-        int p_load = NBUF - 1;   // next tile of the window to load
-        int id_v = ids[p_load < n ? p_load : n - 1];   // its address, read from LDS one step ahead of its use
-        auto issue = [&](TileRegs<FP8> &t) {
-            const int addr = __builtin_amdgcn_readfirstlane(id_v);
-            ++p_load;
-            id_v = ids[p_load < n ? p_load : n - 1];
-            load_tile<FP8>(t, a, k_scale, v_scale, addr, lane, vzero);
-        };
-
-        // Software pipeline over a ring of NBUF tile buffers (fully unrolled: static registers).
-        // The steady-state loop issues its prefetch unconditionally, so the wait before each
-        // compute only covers the tile it needs and NBUF-1 tiles stay in flight; the last few
-        // tiles of a window (and short windows) run through a conditional epilogue.
-        int p = 0;
-        for (; p + 2 * NBUF - 2 < n; p += NBUF) {
-#pragma unroll
-            for (int j = 0; j < NBUF; ++j) {
-                issue(buf[(j + NBUF - 1) % NBUF]);
-                __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of every use of the current tile
-                step(buf[j]);
-            }
-        }
-        // here buf[j] holds tile p + j for j < NBUF-1 (as far as such tiles exist)
-#pragma unroll
-        for (int j = 0; j < 2 * NBUF - 2; ++j) {
-            if (p + j < n) {
-                if (p + j + NBUF - 1 < n) issue(buf[(j + NBUF - 1) % NBUF]);
-                step(buf[j % NBUF]);
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// merge: workgroup (unit, slab) combines the partials of 8 query rows of one unit
-// ---------------------------------------------------------------------------------------------
-constexpr int kMergeRows = 8;
-
-template <int G>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
-{
-    const int slabs = a.rows_pad / kMergeRows;
-    const int unit = blockIdx.x / slabs, slab = blockIdx.x % slabs;
-    const int b = unit / a.num_kv_heads, g = unit % a.num_kv_heads;
-    const int q0 = a.q_indptr[b];
-    const int rows = (a.q_indptr[b + 1] - q0) * G;
-    const int n = slab * kMergeRows + (threadIdx.x >> 5), d4 = threadIdx.x & 31;
-    if (n >= rows) return;
-    const long long total = a.plan->total_tiles;
-    const long long nw = a.plan->num_waves;
-    const int pre = a.tile_prefix[b];
-    const int nb_tiles = a.tile_prefix[b + 1] - pre;
-    const long long off = (long long)pre * a.num_kv_heads + (long long)g * nb_tiles;
-    // wave w covers tiles [w*total/nw, (w+1)*total/nw); the last wave starting at or before tile t
-    // is ((t+1)*nw - 1) / total
-    const int w_first = (int)(((off + 1) * nw - 1) / total);
-    const int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
-
-    // running merge: (m, l, o) <- (m, l, o) (+) partial, both relative to their own reference m
-    float m_all = kNoMax, l_all = 0.f;
-    float4v o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int w = w_first; w <= w_last; ++w) {
-        const long long row = ((long long)w + unit) * a.rows_pad + n;
-        const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + row * 2);
-        const float4v op = *reinterpret_cast<const float4v *>(a.part_o + row * D + d4 * 4);
-        const float m_new = fmaxf(m_all, ml.x);
-        const float wa = exp2f(m_all - m_new), wb = exp2f(ml.x - m_new);  // a partial without visible tokens has l = 0
-        l_all = l_all * wa + ml.y * wb;
-        o = o * wa + op * wb;
-        m_all = m_new;
-    }
-    const float inv = 1.f / l_all;
-    const int qi = n / G, hh = n % G;
-    const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
-    const float2v lo = {o.x * inv, o.y * inv}, hi = {o.z * inv, o.w * inv};
-    uint2 pk;
-    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-    *reinterpret_cast<uint2 *>(static_cast<__bf16 *>(a.out) + orow * D + d4 * 4) = pk;
-    if (a.lse && d4 == 0) a.lse[orow] = (m_all + log2f(l_all)) * kLn2;
-}
-
-template <int G, int NB, bool FP8, bool TREE>
-int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
-{
-    // One wavefront per SIMD (the whole register file, a ring of NBUF tiles): two waves on a SIMD
-    // do not share the memory pipeline fairly under saturation (the older one wins), which turns
-    // into a long tail.
-    constexpr bool QLDS = NB >= 4;
-    constexpr int NBUF = NB <= 3 ? 4 : (NB == 5 && !FP8) ? 2 : 3;
-    const AttnArgs &b = a;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, b);
-    SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
-    // When a profile is being taken the two events are attached to the dispatch itself, so that
-    // their difference is the kernel's own duration on this stream (what a kernel trace shows).
-    hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, QLDS, TREE>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),
-                          dim3(64 * kWavesPerWg), 0, stream, ev0, ev1, 0, b, b.tile_addr, b.wave_desc, b.tile_prefix,
-                          b.kv_len, b.q_indptr, b.k_scale, b.v_scale);
-    SS_HIP_CHECK(hipGetLastError(), "launch attn_stream_kernel");
-    hipLaunchKernelGGL(attn_merge_kernel<G>, dim3((unsigned)a.batch * a.num_kv_heads * (a.rows_pad / kMergeRows)), dim3(256),
-                       0, stream, b);
-    SS_HIP_CHECK(hipGetLastError(), "launch attn_merge_kernel");
-    return SS_OK;
-}
-
-template <int G, int NB>
-int32_t launch_nb(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
-{
-    if (a.tree_mask) {
-        if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true, true>(a, stream, ev0, ev1);
-        return launch_stream<G, NB, false, true>(a, stream, ev0, ev1);
-    }
-    if (a.kv_dtype == SS_FP8_E4M3) return launch_stream<G, NB, true, false>(a, stream, ev0, ev1);
-    return launch_stream<G, NB, false, false>(a, stream, ev0, ev1);
-}
-
-template <int G>
-int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
-{
-    constexpr int NBMAX = (SS_OUT_WIDTH * G + 15) / 16 < kMaxRowBlocks ? (SS_OUT_WIDTH * G + 15) / 16 : kMaxRowBlocks;
-    const int nb = (a.max_q_len * G + 15) / 16;
-    if constexpr (NBMAX >= 5) if (nb == 5) return launch_nb<G, 5>(a, stream, ev0, ev1);
-    if constexpr (NBMAX >= 4) if (nb == 4) return launch_nb<G, 4>(a, stream, ev0, ev1);
-    if constexpr (NBMAX >= 3) if (nb == 3) return launch_nb<G, 3>(a, stream, ev0, ev1);
-    if constexpr (NBMAX >= 2) if (nb == 2) return launch_nb<G, 2>(a, stream, ev0, ev1);
-    return launch_nb<G, 1>(a, stream, ev0, ev1);
-}
-
 }  // namespace
 
 size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim, int launch_waves,
@@ -670,19 +128,23 @@ size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_
 bool attn_mfma_supported(const AttnArgs &a)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
-    return a.head_dim == D && a.q_dtype == SS_BF16 && (a.kv_dtype == SS_BF16 || a.kv_dtype == SS_FP8_E4M3) &&
+    return a.head_dim == kMfmaHeadDim && a.q_dtype == SS_BF16 && (a.kv_dtype == SS_BF16 || a.kv_dtype == SS_FP8_E4M3) &&
            (G == 1 || G == 2 || G == 4 || G == 8) && a.max_q_len * G <= 16 * kMaxRowBlocks &&
            a.launch_waves % kWavesPerWg == 0;
 }
 
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
-    switch (a.num_q_heads / a.num_kv_heads) {
-    case 1: return launch_for_group<1>(a, stream, ev0, ev1);
-    case 2: return launch_for_group<2>(a, stream, ev0, ev1);
-    case 4: return launch_for_group<4>(a, stream, ev0, ev1);
-    case 8: return launch_for_group<8>(a, stream, ev0, ev1);
-    default: return fail(SS_ERR_UNSUPPORTED, "head grouping not built for the MFMA kernel");
+    const int G = a.num_q_heads / a.num_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return fail(SS_ERR_UNSUPPORTED, "head grouping not built for the MFMA kernel");
+    hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, a);
+    SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
+    // the streaming and merge kernels of each grouping live in their own translation unit
+    switch (G) {
+    case 1: return attn_mfma_launch_g1(a, stream, ev0, ev1);
+    case 2: return attn_mfma_launch_g2(a, stream, ev0, ev1);
+    case 4: return attn_mfma_launch_g4(a, stream, ev0, ev1);
+    default: return attn_mfma_launch_g8(a, stream, ev0, ev1);
     }
 }
 

@@ -27,6 +27,8 @@ constexpr int kWavesPerWg = 4;
 constexpr int kMinTilesPerWave = 8;      // below this a KV partition is not worth its partial write
 constexpr int kDescInts = 16;            // ints per wave descriptor
 constexpr int kDescAddrs = 4;            // tile addresses a descriptor carries for the span's first tiles
+constexpr int kMfmaHeadDim = 128;        // head_dim the matrix-core kernel is written for
+constexpr int kMaxRowBlocks = 5;         // 16-row blocks of query rows one wavefront can keep accumulators for
 
 // Written by the plan kernel, read by the streaming and merge kernels.
 struct AttnPlan {
@@ -65,6 +67,10 @@ size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_
                             int launch_waves, int max_q_len);
 bool attn_mfma_supported(const AttnArgs &a);
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
+int32_t attn_mfma_launch_g1(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);   // per head grouping,
+int32_t attn_mfma_launch_g2(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);   // after the plan kernel
+int32_t attn_mfma_launch_g4(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
+int32_t attn_mfma_launch_g8(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 int32_t attn_generic_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1);
 int attn_default_waves();
 
