@@ -10,7 +10,11 @@ pytestmark = pytest.mark.gpu
 TINY, LLAMA8B, RAGGED, LONG, FP8_70B = synth.CONFIGS
 
 
-def run_gpu(inp, max_q_len=0, want_lse=True):
+def run_gpu(inp, max_q_len=None, want_lse=True):
+    """max_q_len None: the batch's own largest row count, as a caller that runs the depth controller
+    passes it; 0: unknown (the library assumes the largest depth it supports)."""
+    if max_q_len is None:
+        max_q_len = int(np.diff(inp["q_indptr"]).max())
     d = binding.attention_to_device(inp)
     out, lse, ws = binding.alloc_attention_outputs(d, max_q_len=max_q_len)
     ws.fill_(0xFF)  # scratch may hold anything (here NaN patterns)
@@ -21,7 +25,7 @@ def run_gpu(inp, max_q_len=0, want_lse=True):
     return o, lse.cpu().numpy().astype(np.float64)
 
 
-def check(inp, oracle, *, max_q_len=0, requests=None, atol=2e-2, rtol=1e-2, label=""):
+def check(inp, oracle, *, max_q_len=None, requests=None, atol=2e-2, rtol=1e-2, label=""):
     """Tolerance of the benchmark spec: |gpu - ref| <= atol + rtol*|ref| (fp8 caches: atol 6e-2)."""
     if inp["kv_dtype"] == "fp8":
         atol = 6e-2

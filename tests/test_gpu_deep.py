@@ -76,3 +76,12 @@ def test_append_and_tree_steps_up_to_depth_20(oracle):
         oracle.kv_compact(inp, ref["accepted_nodes"], ref["accepted_len"])
         for name in ("k_cache", "v_cache"):
             assert np.array_equal(d[name].cpu().numpy().view(np.uint8), inp[name].view(np.uint8)), name
+
+
+def test_unknown_row_bound_is_correct_for_every_grouping(oracle):
+    # max_q_len = 0: the library must assume 21 rows per request; groups of 4 and 8 then exceed what the
+    # matrix-core kernel holds and the call takes the vector kernel by itself
+    for hq, hkv in ((8, 8), (8, 4), (16, 4), (16, 2)):
+        cfg = LLAMA8B.scaled(batch=4, num_q_heads=hq, num_kv_heads=hkv, ctx=("uniform", 30, 500), depth=("uniform", 0, 8))
+        inp = synth.make_attention_inputs(cfg, seed=hq)
+        check(inp, oracle, max_q_len=0, label=f"unknown bound {hq}/{hkv}")
