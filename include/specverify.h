@@ -14,6 +14,13 @@
  *   ss_spec_accept       accept/reject walk over the k drafts and the draw of
  *                        the one new token (residual or bonus distribution)
  *
+ * Around them, the other steps of a decode loop: ss_kv_append (write the new
+ * tokens' K/V before verification), ss_kv_commit (valid lengths after
+ * acceptance), for tree-shaped drafts ss_batch.tree_mask,
+ * ss_spec_accept_tree_greedy and ss_kv_compact, and as host arithmetic the
+ * paper's depth controller (ss_depth_update, Section 3.5) and router
+ * (ss_route_select, Section 3.2).
+ *
  * Conventions for every call
  *   - "device" pointers are HIP device memory on the current device, "host"
  *     pointers ordinary host memory.  The caller owns every buffer, including
