@@ -51,15 +51,22 @@ def cpu_baseline(cfg, att, acc, budget_requests: int):
                target_logits=acc["target_logits"][:rows], draft_logits=acc["draft_logits"][:max(rows - n, 0)],
                draft_tokens=acc["draft_tokens"][:rows - n], u_accept=acc["u_accept"][:rows - n],
                u_sample=acc["u_sample"][:n], temperature=acc["temperature"][:n])
-    t0 = time.perf_counter()
-    oracle.verify_attn(att, requests=reqs)
-    t1 = time.perf_counter()
-    oracle.spec_accept(sub)
-    t2 = time.perf_counter()
+    # whole passes over the sample until about ten seconds of wall time have gone by
+    t_att = t_acc = 0.0
+    passes = 0
+    while passes < 200 and t_att + t_acc < 10.0:
+        t0 = time.perf_counter()
+        oracle.verify_attn(att, requests=reqs)
+        t1 = time.perf_counter()
+        oracle.spec_accept(sub)
+        t2 = time.perf_counter()
+        t_att += t1 - t0
+        t_acc += t2 - t1
+        passes += 1
     toks = rows
-    return dict(value=toks / (t2 - t0), unit="verified tokens/s", cores=oracle.num_threads(), kind="oracle",
-                sample=f"first {n} of {att['batch']} requests ({toks} query tokens): attention {t1 - t0:.2f} s, "
-                       f"accept {t2 - t1:.2f} s")
+    return dict(value=passes * toks / (t_att + t_acc), unit="verified tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"first {n} of {att['batch']} requests ({toks} query tokens), {passes} passes in "
+                       f"{t_att + t_acc:.1f} s: attention {t_att / passes:.3f} s, accept {t_acc / passes:.3f} s per pass")
 
 
 def main() -> int:
