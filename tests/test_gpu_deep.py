@@ -85,3 +85,23 @@ def test_unknown_row_bound_is_correct_for_every_grouping(oracle):
         cfg = LLAMA8B.scaled(batch=4, num_q_heads=hq, num_kv_heads=hkv, ctx=("uniform", 30, 500), depth=("uniform", 0, 8))
         inp = synth.make_attention_inputs(cfg, seed=hq)
         check(inp, oracle, max_q_len=0, label=f"unknown bound {hq}/{hkv}")
+
+
+def test_batches_larger_than_a_workgroup(oracle):
+    # 300 requests: every per-request loop that strides by the workgroup size takes a second trip
+    cfg = LLAMA8B.scaled(batch=300, vocab=2500, ctx=("uniform", 5, 90), depth=("uniform", 0, 8))
+    inp = synth.make_append_inputs(cfg, seed=6)
+    append_and_compare(inp, oracle, "300 requests: append")
+    check(inp, oracle, label="300 requests: attention")
+    binding.ss_set_option("validate", 1)
+    try:
+        check(inp, oracle, label="300 requests: attention, validated")
+    finally:
+        binding.ss_set_option("validate", 0)
+    acc_in = synth.make_accept_inputs(cfg, seed=6, depth=inp["depth"], row_pad=(-2500) % 8)
+    compare_accept(acc_in, oracle, label="300 requests: accept")
+    d = binding.attention_to_device(inp)
+    n = binding._to_dev(oracle.spec_accept(acc_in)["accepted_len"], "cuda:0")
+    binding.ss_kv_commit(d["q_indptr"], n, d["kv_len"])
+    torch.cuda.synchronize()
+    assert np.array_equal(d["kv_len"].cpu().numpy(), oracle.kv_commit(inp["q_indptr"], n.cpu().numpy(), inp["kv_len"]))
