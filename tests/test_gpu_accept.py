@@ -186,3 +186,5 @@ def test_full_size_configs(oracle, cfg):
     compare(inp, oracle, label=cfg.name)
     if cfg is LLAMA8B:
         compare(synth.make_accept_inputs(cfg, seed=0, greedy=True), oracle, label=cfg.name + " greedy")
+        for seed in (1, 2):
+            compare(synth.make_accept_inputs(cfg, seed=seed), oracle, label=f"{cfg.name} seed {seed}")

@@ -156,3 +156,9 @@ def test_full_size_configs_sampled(oracle, cfg, max_q_len, nreq):
     inp = synth.make_attention_inputs(cfg, seed=0)
     reqs = _sampled_requests(inp, nreq)
     check(inp, oracle, max_q_len=max_q_len, requests=reqs, label=cfg.name)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_bench_workload_other_seeds(oracle, seed):
+    inp = synth.make_attention_inputs(LLAMA8B, seed=seed)
+    check(inp, oracle, max_q_len=5, requests=_sampled_requests(inp, 6), label=f"{LLAMA8B.name} seed {seed}")
