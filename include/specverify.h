@@ -144,10 +144,11 @@ size_t ss_spec_verify_attn_workspace(const ss_paged_kv *kv, const ss_batch *batc
  *
  * Internally the KV stream is cut into partitions that are reduced independently and merged
  * by their log-sum-exp; the result does not depend on the partitioning beyond fp32 rounding.
- * The matrix-core kernel covers head_dim 128, bf16 queries, bf16 or e4m3 caches, 1/2/4/8 query heads per
- * KV head and max_q_len * (query heads per KV head) <= 80 query rows per KV head (depth 8 for groups of 8,
- * depth 19 for groups of 4, any depth for smaller groups); everything else takes a plain fp32 vector
- * kernel that has no such limits and is several times slower.
+ * The matrix-core kernel covers head_dim 128, bf16 queries, bf16 or e4m3 caches and 1/2/4/8 query heads per
+ * KV head.  One pass over the cache serves up to 80 query rows per KV head (max_q_len * heads per KV head:
+ * depth 9 for groups of 8, depth 19 for groups of 4, any depth for smaller groups); a larger bound is
+ * served in two or three passes over equal windows of query tokens, each reading the cache again.
+ * Everything else takes a plain fp32 vector kernel that has no shape limits and is far slower.
  * batch == 0 or total_rows == 0 is a no-op returning SS_OK.
  */
 int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const void *q, int32_t q_dtype,

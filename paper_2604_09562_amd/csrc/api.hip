@@ -156,8 +156,10 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.sm_scale = sm_scale;
     a.launch_waves = launch_waves;
     const int G = num_q_heads / kv->num_kv_heads;
-    a.rows_pad = (int)align_up((size_t)max_q_len * G, 16);
+    a.rows_pad = attn_rows_pad(max_q_len, G);
     a.max_q_len = max_q_len;
+    a.q_lo = 0;
+    a.q_win = max_q_len;
     // carve the workspace
     char *w = static_cast<char *>(workspace);
     a.plan = reinterpret_cast<AttnPlan *>(w);

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     const int tid = threadIdx.x;
     int before = 0, rest = 0;   // tiles (per kv head) of the requests in front of b, and from b on
     for (int i = tid; i < a.batch; i += 256) {
-        const int t = (a.kv_len[i] + kTile - 1) / kTile;
+        const int t = window_tiles(a.kv_len[i], a.q_indptr[i + 1] - a.q_indptr[i], a.q_lo);
         if (i < b) before += t; else rest += t;
     }
     for (int off = 32; off; off >>= 1) {
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     if (nw < 1) nw = 1;
     if (nw > a.launch_waves) nw = a.launch_waves;
 
-    const int n = (a.kv_len[b] + kTile - 1) / kTile;
+    const int n = window_tiles(a.kv_len[b], a.q_indptr[b + 1] - a.q_indptr[b], a.q_lo);
     const long long off = (long long)pre * a.num_kv_heads + (long long)g * n;   // this unit's place in the flat list
     const int32_t *bt = a.block_table + (long long)b * a.max_blocks;
     int32_t *dst = a.tile_addr + off;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
                 if (++gg == a.num_kv_heads) {
                     gg = 0;
                     if (++bb < a.batch) {
-                        nn = (a.kv_len[bb] + kTile - 1) / kTile;
+                        nn = window_tiles(a.kv_len[bb], a.q_indptr[bb + 1] - a.q_indptr[bb], a.q_lo);
                         tb = a.block_table + (long long)bb * a.max_blocks;
                     }
                 }
@@ -114,7 +114,7 @@ size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_
                             int max_q_len)
 {
     const int G = num_q_heads / num_kv_heads;
-    const size_t rows_pad = align_up((size_t)max_q_len * G, 16);
+    const size_t rows_pad = (size_t)attn_rows_pad(max_q_len, G);
     const size_t slots = (size_t)launch_waves + (size_t)batch * num_kv_heads;
     size_t n = 256;
     n += align_up(sizeof(int32_t) * ((size_t)batch + 1), 256);
@@ -129,23 +129,36 @@ bool attn_mfma_supported(const AttnArgs &a)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
     return a.head_dim == kMfmaHeadDim && a.q_dtype == SS_BF16 && (a.kv_dtype == SS_BF16 || a.kv_dtype == SS_FP8_E4M3) &&
-           (G == 1 || G == 2 || G == 4 || G == 8) && a.max_q_len * G <= 16 * kMaxRowBlocks &&
-           a.launch_waves % kWavesPerWg == 0;
+           (G == 1 || G == 2 || G == 4 || G == 8) && a.launch_waves % kWavesPerWg == 0;
 }
 
 int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
     const int G = a.num_q_heads / a.num_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return fail(SS_ERR_UNSUPPORTED, "head grouping not built for the MFMA kernel");
-    hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, a);
-    SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
-    // the streaming and merge kernels of each grouping live in their own translation unit
-    switch (G) {
-    case 1: return attn_mfma_launch_g1(a, stream, ev0, ev1);
-    case 2: return attn_mfma_launch_g2(a, stream, ev0, ev1);
-    case 4: return attn_mfma_launch_g4(a, stream, ev0, ev1);
-    default: return attn_mfma_launch_g8(a, stream, ev0, ev1);
+    // A wavefront holds at most 16 * kMaxRowBlocks query rows of a KV head.  A batch whose row bound
+    // exceeds that is served in several passes over equal windows of query tokens, each a full
+    // plan / stream / merge sequence on the same workspace (the stream orders them).
+    const int win_max = 16 * kMaxRowBlocks / G;
+    const int passes = (a.max_q_len + win_max - 1) / win_max;
+    AttnArgs p = a;
+    p.q_win = (a.max_q_len + passes - 1) / passes;
+    for (p.q_lo = 0; p.q_lo < a.max_q_len; p.q_lo += p.q_win) {
+        hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, p);
+        SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
+        // the streaming and merge kernels of each grouping live in their own translation unit; a
+        // profile's event pair goes to the first pass
+        hipEvent_t e0 = p.q_lo ? nullptr : ev0, e1 = p.q_lo ? nullptr : ev1;
+        int32_t rc;
+        switch (G) {
+        case 1: rc = attn_mfma_launch_g1(p, stream, e0, e1); break;
+        case 2: rc = attn_mfma_launch_g2(p, stream, e0, e1); break;
+        case 4: rc = attn_mfma_launch_g4(p, stream, e0, e1); break;
+        default: rc = attn_mfma_launch_g8(p, stream, e0, e1); break;
+        }
+        if (rc != SS_OK) return rc;
     }
+    return SS_OK;
 }
 
 }  // namespace ss

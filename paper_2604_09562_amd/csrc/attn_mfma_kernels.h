@@ -174,8 +174,9 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         L = meta_L;
         q0 = meta_q0;
         q_len = meta_q1 - meta_q0;
+        const int q_here = window_q_len(q_len, a.q_lo, a.q_win);   // query tokens of this pass's window
         nb_tiles = meta_nbt;
-        rows = q_len * G;
+        rows = q_here * G;
         nbu = (rows + 15) >> 4;
         ctx = L - q_len;
         {
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         for (int nb = 0; nb < NB; ++nb) {
             const int n = nb * 16 + r16;
             const bool ok = n < rows;
-            const int qi = n / G, hh = n % G;
+            const int qi = a.q_lo + n / G, hh = n % G;   // query token within the request, head within the group
             if constexpr (TREE)   // padding rows see every new token: harmless, and no row is empty
                 newmask[nb] = ok ? a.tree_mask[q0 + qi] : (2u << (q_len - 1)) - 1u;
             else
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     const int unit = blockIdx.x / slabs, slab = blockIdx.x % slabs;
     const int b = unit / a.num_kv_heads, g = unit % a.num_kv_heads;
     const int q0 = a.q_indptr[b];
-    const int rows = (a.q_indptr[b + 1] - q0) * G;
+    const int rows = window_q_len(a.q_indptr[b + 1] - q0, a.q_lo, a.q_win) * G;   // rows of this pass's window
     const int n = slab * kMergeRows + (threadIdx.x >> 5), d4 = threadIdx.x & 31;
     if (n >= rows) return;
     const long long total = a.plan->total_tiles;
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
         m_all = m_new;
     }
     const float inv = 1.f / l_all;
-    const int qi = n / G, hh = n % G;
+    const int qi = a.q_lo + n / G, hh = n % G;
     const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
     const float2v lo = {o.x * inv, o.y * inv}, hi = {o.z * inv, o.w * inv};
     uint2 pk;
@@ -560,7 +561,7 @@ template <int G>
 int32_t launch_for_group(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hipEvent_t ev1)
 {
     constexpr int NBMAX = (SS_OUT_WIDTH * G + 15) / 16 < kMaxRowBlocks ? (SS_OUT_WIDTH * G + 15) / 16 : kMaxRowBlocks;
-    const int nb = (a.max_q_len * G + 15) / 16;
+    const int nb = (a.q_win * G + 15) / 16;   // row blocks of one pass's window
     if constexpr (NBMAX >= 5) if (nb == 5) return launch_nb<G, 5>(a, stream, ev0, ev1);
     if constexpr (NBMAX >= 4) if (nb == 4) return launch_nb<G, 4>(a, stream, ev0, ev1);
     if constexpr (NBMAX >= 3) if (nb == 3) return launch_nb<G, 3>(a, stream, ev0, ev1);

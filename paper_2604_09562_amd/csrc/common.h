@@ -30,6 +30,26 @@ constexpr int kDescAddrs = 4;            // tile addresses a descriptor carries 
 constexpr int kMfmaHeadDim = 128;        // head_dim the matrix-core kernel is written for
 constexpr int kMaxRowBlocks = 5;         // 16-row blocks of query rows one wavefront can keep accumulators for
 
+// Query tokens of a request that fall into the pass's window, and the KV tiles its units stream in this
+// pass: a request without rows in the window keeps one tile so that no unit of the flat tile space is empty.
+__host__ __device__ inline int window_q_len(int q_len, int q_lo, int q_win)
+{
+    const int n = q_len - q_lo;
+    return n < 0 ? 0 : (n > q_win ? q_win : n);
+}
+// Query rows per (request, KV head) that the partial slots are sized for: the hinted bound, or one pass's window.
+inline int attn_rows_pad(int max_q_len, int G)
+{
+    const int cap = 16 * kMaxRowBlocks, rows = max_q_len * G;
+    if (rows <= cap || cap / G == 0) return (int)align_up((size_t)rows, 16);
+    const int win_max = cap / G, passes = (max_q_len + win_max - 1) / win_max;
+    return (int)align_up((size_t)((max_q_len + passes - 1) / passes) * G, 16);
+}
+__host__ __device__ inline int window_tiles(int kv_len, int q_len, int q_lo)
+{
+    return q_len > q_lo ? (kv_len + kTile - 1) / kTile : 1;
+}
+
 // Written by the plan kernel, read by the streaming and merge kernels.
 struct AttnPlan {
     int32_t total_tiles;   // sum over requests of ceil(kv_len/16) * num_kv_heads
@@ -51,6 +71,10 @@ struct AttnArgs {
     void *out;
     float *lse;
     int32_t q_dtype, num_q_heads, total_rows, max_q_len;
+    // Query-token window of this pass: the kernels compute query tokens q_lo .. q_lo+q_win-1 of every
+    // request (those it has).  One pass covers everything unless a request can bring more rows per KV
+    // head than a wavefront holds; then the launcher walks the windows one after the other.
+    int32_t q_lo, q_win;
     float sm_scale;
     // workspace carve-up
     AttnPlan *plan;
