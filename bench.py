@@ -83,6 +83,8 @@ def main() -> int:
                     help="after timing, launch a plain device copy of this size three times: the known-size "
                          "kernel that scales FETCH_SIZE / WRITE_SIZE in a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
+    ap.add_argument("--depth", type=int, default=-1,
+                    help="give every request this draft depth instead of the workload's own (0..20; for what-if runs)")
     ap.add_argument("--tree", action="store_true",
                     help="the drafts of every request form a random tree instead of a chain (same shapes and sizes)")
     ap.add_argument("--attn-waves", type=int, default=0, help="KV partitions of the attention kernel (0 = automatic)")
@@ -102,6 +104,8 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 3
     cfg = synth.config_by_name(args.config)
+    if args.depth >= 0:
+        cfg = cfg.scaled(name=f"{cfg.name}_k{args.depth}", depth=("fixed", args.depth))
     if args.attn_waves:
         binding.ss_set_option("attn_waves", args.attn_waves)
     dev = "cuda:0"
