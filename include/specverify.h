@@ -96,6 +96,12 @@ typedef struct ss_paged_kv {
  *                this step, plus one), or 0 if unknown (SS_OUT_WIDTH is assumed).  A tight bound lets the
  *                library pick a kernel with fewer padded query rows; a bound that some request
  *                exceeds is a caller error (rows beyond it are not computed).
+ *   flags        SS_BATCH_REUSE_PLAN tells ss_spec_verify_attn that its workspace still holds the plan an
+ *                earlier call built for exactly this batch (same block_table, kv_len, q_indptr contents,
+ *                same max_q_len, head counts and workspace; only q, the cache contents and the outputs
+ *                may differ): the layers of one decode step share their batch, so all but the first
+ *                can skip the plan kernel.  Ignored where no stored plan can serve (the vector kernel,
+ *                or a row bound that takes several passes).  Other calls ignore the field.
  *   tree_mask    NULL: the new tokens of a request form a chain (row i attends new tokens 0..i).
  *                Otherwise device uint32 [total rows]: the new tokens form a draft tree (the dynamic
  *                draft trees of the speculative systems the paper builds on, Section 2.2) with row 0
@@ -104,11 +110,13 @@ typedef struct ss_paged_kv {
  *                Every row's own bit must be set and no bit at or above q_len; the context before the new
  *                tokens is always visible.  Read by ss_spec_verify_attn only.
  */
+#define SS_BATCH_REUSE_PLAN 1
+
 typedef struct ss_batch {
     int32_t batch;
     int32_t max_blocks_per_seq;
     int32_t max_q_len;
-    int32_t reserved; /* must be 0 */
+    int32_t flags;    /* 0 or SS_BATCH_REUSE_PLAN */
     const int32_t *block_table;
     const int32_t *kv_len;
     const int32_t *q_indptr;

@@ -40,7 +40,7 @@ class ss_paged_kv(ctypes.Structure):
 
 class ss_batch(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
-                ("max_q_len", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("max_q_len", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("block_table", ctypes.c_void_p), ("kv_len", ctypes.c_void_p), ("q_indptr", ctypes.c_void_p),
                 ("tree_mask", ctypes.c_void_p)]
 
@@ -190,12 +190,15 @@ def accept_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, objec
     return d
 
 
-def _descriptors(d: Dict[str, object], max_q_len: int):
+SS_BATCH_REUSE_PLAN = 1
+
+
+def _descriptors(d: Dict[str, object], max_q_len: int, flags: int = 0):
     kv = ss_paged_kv(d["num_blocks"], d["block_size"], d["num_kv_heads"], d["head_dim"], _DT[d["kv_dtype"]],
                      d["k_cache"].data_ptr(), d["v_cache"].data_ptr(),
                      0 if d["k_scale"] is None else d["k_scale"].data_ptr(),
                      0 if d["v_scale"] is None else d["v_scale"].data_ptr())
-    bt = ss_batch(d["batch"], d["max_blocks_per_seq"], max_q_len, 0, d["block_table"].data_ptr(),
+    bt = ss_batch(d["batch"], d["max_blocks_per_seq"], max_q_len, flags, d["block_table"].data_ptr(),
                   d["kv_len"].data_ptr(), d["q_indptr"].data_ptr(),
                   d["tree_mask"].data_ptr() if d.get("tree_mask") is not None else 0)
     return kv, bt
@@ -210,9 +213,9 @@ def ss_spec_verify_attn_workspace(d: Dict[str, object], max_q_len: int = 0) -> i
 
 
 def ss_spec_verify_attn(d: Dict[str, object], out: torch.Tensor, lse: Optional[torch.Tensor],
-                        workspace: torch.Tensor, max_q_len: int = 0) -> None:
+                        workspace: torch.Tensor, max_q_len: int = 0, reuse_plan: bool = False) -> None:
     """Enqueue verify attention for a device batch; `out`/`lse`/`workspace` are caller-owned device tensors."""
-    kv, bt = _descriptors(d, max_q_len)
+    kv, bt = _descriptors(d, max_q_len, SS_BATCH_REUSE_PLAN if reuse_plan else 0)
     _check(lib().ss_spec_verify_attn(ctypes.byref(kv), ctypes.byref(bt), _ptr(d["q"]), _DT[d["q_dtype"]],
                                      d["num_q_heads"], d["total_rows"], ctypes.c_float(d["sm_scale"]), _ptr(out),
                                      _ptr(lse), _ptr(workspace), workspace.numel() * workspace.element_size(),

@@ -58,8 +58,9 @@ static int32_t check_attn_shape(const ss_paged_kv *kv, const ss_batch *b, int32_
     if ((int64_t)kv->num_blocks * kv->num_kv_heads > 0x7fffffffll ||
         (int64_t)b->batch * b->max_blocks_per_seq * kv->num_kv_heads > 0x7fffffffll)
         return fail(SS_ERR_UNSUPPORTED, "num_blocks * num_kv_heads and batch * max_blocks * num_kv_heads must fit 31 bits");
-    if (b->max_q_len < 0 || b->max_q_len > SS_OUT_WIDTH || b->reserved != 0)
-        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d], reserved must be 0", SS_OUT_WIDTH);
+    if (b->max_q_len < 0 || b->max_q_len > SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
+    if (b->flags & ~SS_BATCH_REUSE_PLAN) return fail(SS_ERR_INVALID_ARG, "unknown bits in ss_batch.flags (%d)", b->flags);
     return SS_OK;
 }
 
@@ -160,6 +161,7 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.max_q_len = max_q_len;
     a.q_lo = 0;
     a.q_win = max_q_len;
+    a.reuse_plan = (batch->flags & SS_BATCH_REUSE_PLAN) ? 1 : 0;
     // carve the workspace
     char *w = static_cast<char *>(workspace);
     a.plan = reinterpret_cast<AttnPlan *>(w);

@@ -144,8 +144,10 @@ int32_t attn_mfma_launch(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, 
     AttnArgs p = a;
     p.q_win = (a.max_q_len + passes - 1) / passes;
     for (p.q_lo = 0; p.q_lo < a.max_q_len; p.q_lo += p.q_win) {
-        hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, p);
-        SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
+        if (!(a.reuse_plan && passes == 1)) {   // a stored plan describes one window only
+            hipLaunchKernelGGL(attn_plan_kernel, dim3((unsigned)a.batch * a.num_kv_heads), dim3(256), 0, stream, p);
+            SS_HIP_CHECK(hipGetLastError(), "launch attn_plan_kernel");
+        }
         // the streaming and merge kernels of each grouping live in their own translation unit; a
         // profile's event pair goes to the first pass
         hipEvent_t e0 = p.q_lo ? nullptr : ev0, e1 = p.q_lo ? nullptr : ev1;

@@ -75,6 +75,7 @@ struct AttnArgs {
     // request (those it has).  One pass covers everything unless a request can bring more rows per KV
     // head than a wavefront holds; then the launcher walks the windows one after the other.
     int32_t q_lo, q_win;
+    int32_t reuse_plan;    // the workspace already holds this batch's plan (single-pass launches only)
     float sm_scale;
     // workspace carve-up
     AttnPlan *plan;

@@ -113,6 +113,37 @@ def test_large_scores(oracle):
     check(inp, oracle, label="large scores")
 
 
+def test_plan_reuse_across_layers(oracle):
+    # Two "layers" of one decode step: the same batch metadata and workspace, different queries and
+    # cache contents.  The second call skips the plan kernel and must still match the oracle; with a
+    # row bound that needs several passes the flag is ignored and the result is right all the same.
+    for cfg, depth in ((LLAMA8B.scaled(batch=9, ctx=("uniform", 30, 2500), depth=("uniform", 0, 8)), None),
+                       (FP8_70B.scaled(batch=5, ctx=("uniform", 30, 800)), np.array([20, 3, 11, 0, 16], np.int32))):
+        kw = {} if depth is None else dict(depth=depth, kv_len=np.array([300, 41, 800, 17, 129], np.int32))
+        layer0 = synth.make_attention_inputs(cfg, seed=8, **kw)
+        layer1 = dict(layer0, k_cache=layer0["v_cache"], v_cache=layer0["k_cache"],      # other contents, same layout
+                      q=synth.to_bf16_bits(-synth.decode_storage(layer0["q"], "bf16")))
+        if cfg.kv_dtype == "fp8":
+            layer1.update(k_scale=layer0["v_scale"], v_scale=layer0["k_scale"])
+        mq = int(np.diff(layer0["q_indptr"]).max())
+        d0, d1 = binding.attention_to_device(layer0), binding.attention_to_device(layer1)
+        out, lse, ws = binding.alloc_attention_outputs(d0, max_q_len=mq)
+        binding.ss_spec_verify_attn(d0, out, lse, ws, max_q_len=mq)
+        for name in ("block_table", "kv_len", "q_indptr"):    # the very same metadata arrays
+            d1[name] = d0[name]
+        out1 = torch.empty_like(out)
+        binding.ss_spec_verify_attn(d1, out1, lse, ws, max_q_len=mq, reuse_plan=True)
+        torch.cuda.synchronize()
+        ref, _ = oracle.verify_attn(layer1)
+        got = binding.bf16_bits_to_float(out1)
+        atol = 6e-2 if cfg.kv_dtype == "fp8" else 2e-2
+        assert np.all(np.abs(got - ref) <= atol + 1e-2 * np.abs(ref)), cfg.name
+        fresh = torch.empty_like(out)
+        binding.ss_spec_verify_attn(d1, fresh, lse, ws, max_q_len=mq)
+        torch.cuda.synchronize()
+        assert torch.equal(fresh, out1), "a reused plan must give the bits a fresh one gives"
+
+
 def test_empty_batch_is_noop():
     cfg = LLAMA8B.scaled(batch=2, ctx=("fixed", (40,)))
     inp = synth.make_attention_inputs(cfg, seed=0)
