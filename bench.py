@@ -83,6 +83,9 @@ def main() -> int:
                     help="after timing, launch a plain device copy of this size three times: the known-size "
                          "kernel that scales FETCH_SIZE / WRITE_SIZE in a rocprofv3 --pmc run of this command")
     ap.add_argument("--no-check", action="store_true", help="skip the parity spot check after timing")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step from a captured HIP graph (the kernel durations of the roofline entry "
+                         "then come from an eager pass after the timed region)")
     ap.add_argument("--depth", type=int, default=-1,
                     help="give every request this draft depth instead of the workload's own (0..20; for what-if runs)")
     ap.add_argument("--tree", action="store_true",
@@ -131,13 +134,37 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    binding.ss_profile_begin(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        # one graph per rotated copy, captured on a side stream; the timed loop only replays
+        graphs, side = [], torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for r in range(nrot):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step(r)
+                graphs.append(g)
+        torch.cuda.current_stream().wait_stream(side)
+        for r in range(nrot):
+            graphs[r].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % nrot].replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        binding.ss_profile_begin(args.steps)
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+    else:
+        binding.ss_profile_begin(args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     kern_ms = binding.ss_profile_collect(args.steps)
     elapsed = t1 - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -185,7 +212,8 @@ def main() -> int:
                    "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "query_tokens": q_tokens,
                    "kv_tokens": int(att["kv_len"].astype(np.int64).sum()), "vocab": cfg.vocab,
                    "max_q_len": max_q_len, "rotated_copies": nrot, "seed": args.seed,
-                   "drafts": "tree" if args.tree else "chain"},
+                   "drafts": "tree" if args.tree else "chain",
+                   "launch": "graph replay" if args.graph else "eager"},
         "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg.name),
                      "algorithmic_bytes": kv_bytes, "kernel_ms_avg": kern_avg_ms,
