@@ -163,6 +163,9 @@ def _to_dev(a: Optional[np.ndarray], device) -> Optional[torch.Tensor]:
     return torch.from_numpy(a).to(device)
 
 
+to_device = _to_dev   # one array (numpy storage format) -> device tensor, bytes unchanged
+
+
 def attention_to_device(inp: Dict[str, object], device="cuda:0") -> Dict[str, object]:
     """Copy one attention batch (dict of numpy storage arrays) to the GPU, bytes unchanged."""
     d = dict(inp)
