@@ -5,7 +5,8 @@
 // (greedy mode: maximum and lowest-index argmax of target rows only).
 // decide      one workgroup per request merges the chunk statistics of all its rows in parallel,
 //             evaluates u < p/q for every draft in fp64 and fixes the accepted length and the
-//             row(s) the new token is drawn from.
+//             row(s) the new token is drawn from; in greedy mode it compares arg-maxima instead,
+//             along the chain or, given parent pointers, down a draft tree.
 // Passes 2a-2b touch only those one or two rows per request and work in fp64, so that the drawn
 // token can be reproduced by an fp64 reference.  2a leaves, per 2048-entry block, the sums of the
 // unnormalised exponentials of both rows (the exact normalisers Zp, Zq once added up) and the same
@@ -459,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
     if (lane < SS_OUT_WIDTH) {
         int tok = lane < n ? x : -1;
         if (a.greedy && lane == n) tok = row_arg[n];
-        a.out_tokens[(int64_t)b * SS_OUT_WIDTH + lane] = tok;   // slot n is filled by pass 2c when sampling
+        a.out_tokens[(int64_t)b * SS_OUT_WIDTH + lane] = tok;   // slot n is filled by pass 2b when sampling
     }
     if (lane == 0) {
         a.accepted_len[b] = n;
