@@ -45,6 +45,7 @@ def _load():
         lib.oracle_kv_commit.restype = ctypes.c_int
         lib.oracle_tree_accept_greedy.restype = ctypes.c_int
         lib.oracle_kv_compact.restype = ctypes.c_int
+        lib.oracle_tree_accept_sample.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -133,6 +134,25 @@ def tree_accept_greedy(inp: Dict[str, object]) -> Dict[str, np.ndarray]:
     if rc != 0:
         raise ValueError(f"oracle_tree_accept_greedy rejected its arguments (code {rc})")
     return dict(accepted_len=accepted, out_tokens=toks, accepted_nodes=nodes)
+
+
+def tree_accept_sample(inp: Dict[str, object], tie_eps: float = 1e-5) -> Dict[str, np.ndarray]:
+    """Sampled acceptance walk over the draft trees of a batch dict from ``synth.make_tree_accept_inputs``."""
+    B, Rd = inp["batch"], inp["total_rows"] - inp["batch"]
+    accepted = np.full(B, -99, dtype=np.int32)
+    toks = np.full((B, OUT_WIDTH), -99, dtype=np.int32)
+    nodes = np.full((B, OUT_WIDTH - 1), -99, dtype=np.int32)
+    ratio = np.full(max(Rd, 1), np.nan, dtype=np.float64)
+    near = np.zeros(max(Rd, 1), dtype=np.int32)
+    rc = _load().oracle_tree_accept_sample(
+        ctypes.c_int(B), ctypes.c_int(inp["vocab"]), ctypes.c_int64(inp["row_stride"]),
+        ctypes.c_int(_DT[inp["logit_dtype"]]), _p(inp["q_indptr"]), _p(inp["tree_parent"]),
+        _p(inp["target_logits"]), _p(inp["draft_logits"]), _p(inp["draft_tokens"]), _p(inp["u_accept"]),
+        _p(inp["u_sample"]), _p(inp["temperature"]), ctypes.c_int(OUT_WIDTH), ctypes.c_double(tie_eps),
+        _p(accepted), _p(toks), _p(nodes), _p(ratio), _p(near))
+    if rc != 0:
+        raise ValueError(f"oracle_tree_accept_sample rejected its arguments (code {rc})")
+    return dict(accepted_len=accepted, out_tokens=toks, accepted_nodes=nodes, ratio=ratio[:Rd], near_tie=near[:Rd])
 
 
 def encode(x: np.ndarray, dtype: str) -> np.ndarray:

@@ -509,6 +509,133 @@ int oracle_tree_accept_greedy(int B, int V, int64_t row_stride, int logit_dtype,
     return 0;
 }
 
+/* ---- sampled acceptance over a draft tree --------------------------------------
+ *
+ * Tree layout as for the greedy walk.  Draft row c-1 of the request (row q_indptr[b]-b+c-1 of
+ * draft_logits) is the distribution node c's token x_c was drawn from, u_c = u_accept at the same
+ * index its uniform.  The walk keeps a current node and a current distribution r, starting at node 0
+ * with r = p_0 = softmax(target row 0 / T), and offers r the children of the current node one after
+ * the other, in node order, each as one step of speculative sampling against its own proposal
+ * q_c = softmax(draft row of c / T):
+ *
+ *     accept c  iff  u_c * q_c[x_c] < r[x_c]      (u_c < min(1, r/q))
+ *     accepted: c becomes the current node, r = p_c, and its children are offered next
+ *     rejected: r <- max(0, r - q_c) / S,  S = sum_v max(0, r_v - q_c,v)   (unchanged if S == 0),
+ *               and the next sibling is offered
+ *     no child left: draw y from r by the inverse CDF in token order with u_s (first v whose
+ *               running sum exceeds u_s * sum(r); if rounding leaves none, the last v with mass);
+ *               if the last rejection found S == 0 (r equal to the proposal), y is the
+ *               lowest-index argmax of the current node's target row, as in the chain rule.
+ *
+ * Every step is the accept/residual step of speculative sampling applied to the distribution the
+ * previous step left, so the emitted tokens are distributed as plain sampling from the target; a
+ * chain reduces to oracle_spec_accept.  Outputs as for the greedy walk, plus per draft node the
+ * ratio r[x]/q[x] it was offered at (NaN for nodes the walk never offered) and the near-tie flag.
+ */
+int oracle_tree_accept_sample(int B, int V, int64_t row_stride, int logit_dtype, const int32_t *q_indptr,
+                              const int32_t *tree_parent, const void *target_logits, const void *draft_logits,
+                              const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                              const float *temperature, int out_width, double tie_eps, int32_t *accepted_len,
+                              int32_t *out_tokens, int32_t *accepted_nodes, double *ratio, int32_t *near_tie)
+{
+    if (B < 0 || V <= 0 || row_stride < V || out_width < 1)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (k < 0 || k + 1 > out_width || tree_parent[q_indptr[b]] != -1 || !(temperature[b] > 0.0f))
+            return -4;
+        for (int i = 1; i <= k; ++i) {
+            int par = tree_parent[q_indptr[b] + i], x = draft_tokens[q_indptr[b] - b + i - 1];
+            if (par < 0 || par >= i || x < 0 || x >= V)
+                return -6;
+        }
+    }
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int64_t row0 = q_indptr[b], d0 = q_indptr[b] - b;
+        int k = q_indptr[b + 1] - q_indptr[b] - 1;
+        double T = (double)temperature[b];
+        int32_t *toks = out_tokens + (int64_t)b * out_width;
+        int32_t *nodes = accepted_nodes + (int64_t)b * (out_width - 1);
+        for (int j = 0; j < out_width; ++j)
+            toks[j] = -1;
+        for (int j = 0; j < out_width - 1; ++j)
+            nodes[j] = -1;
+        for (int i = 0; i < k; ++i) {
+            if (ratio) ratio[d0 + i] = NAN;
+            if (near_tie) near_tie[d0 + i] = 0;
+        }
+        double *r = (double *)malloc(sizeof(double) * (size_t)V * 2);
+        if (!r) {
+            fail = 1;
+            continue;
+        }
+        double *q = r + V;
+        int cur = 0, n = 0, degenerate = 0;
+        softmax_row(target_logits, row0 * row_stride, V, logit_dtype, T, r);
+        for (;;) {
+            int moved = 0;
+            for (int c = cur + 1; c <= k && !moved; ++c) {
+                if (tree_parent[row0 + c] != cur)
+                    continue;
+                int x = draft_tokens[d0 + c - 1];
+                double u = (double)u_accept[d0 + c - 1];
+                softmax_row(draft_logits, (d0 + c - 1) * row_stride, V, logit_dtype, T, q);
+                double rho = r[x] / q[x];
+                if (ratio) ratio[d0 + c - 1] = rho;
+                if (near_tie) {
+                    double capped = rho < 1.0 ? rho : 1.0;
+                    near_tie[d0 + c - 1] = (rho == rho) && fabs(u - capped) < tie_eps && rho < 1.0 + tie_eps;
+                }
+                if (u * q[x] < r[x]) {
+                    toks[n] = x;
+                    nodes[n] = c;
+                    ++n;
+                    cur = c;
+                    degenerate = 0;
+                    softmax_row(target_logits, (row0 + c) * row_stride, V, logit_dtype, T, r);
+                    moved = 1;
+                } else {
+                    double S = 0.0;
+                    for (int v = 0; v < V; ++v)
+                        S += r[v] > q[v] ? r[v] - q[v] : 0.0;
+                    degenerate = !(S > 0.0);
+                    if (!degenerate)
+                        for (int v = 0; v < V; ++v)
+                            r[v] = (r[v] > q[v] ? r[v] - q[v] : 0.0) / S;
+                }
+            }
+            if (!moved)
+                break;
+        }
+        int y = -1;
+        if (degenerate) {
+            y = argmax_row(target_logits, (row0 + cur) * row_stride, V, logit_dtype);
+        } else {
+            double S = 0.0, c = 0.0;
+            for (int v = 0; v < V; ++v)
+                S += r[v];
+            double thr = (double)u_sample[b] * S;
+            int last_pos = -1;
+            for (int v = 0; v < V; ++v) {
+                if (!(r[v] > 0.0))
+                    continue;
+                c += r[v];
+                last_pos = v;
+                if (y < 0 && c > thr)
+                    y = v;
+            }
+            if (y < 0)
+                y = last_pos;
+        }
+        toks[n] = y;
+        accepted_len[b] = n;
+        free(r);
+    }
+    return fail ? -5 : 0;
+}
+
 /* ---- KV append and commit (the steps around verification) --------------------
  *
  * Section 3.4, Eq. 7: the decode worker's KV is the prefill KV with every new
