@@ -212,14 +212,42 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
  *   accepted_nodes[b]  device int32 [batch][SS_MAX_DEPTH]: the accepted node numbers in path order,
  *                      -1 beyond n (what a cache compaction needs)
  *   tree_parent        device int32 [total_rows]; -1 for every request's node 0
- * Other arguments, the workspace (ss_spec_accept_workspace) and errors as for ss_spec_accept.  Only the
- * greedy rule is provided for trees: the sampled rule needs one residual distribution per rejected
- * sibling, a chain of full-vocabulary passes this library does not implement.
+ * Other arguments, the workspace (ss_spec_accept_workspace) and errors as for ss_spec_accept.
  */
 int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
                                    int32_t total_rows, int32_t max_q_len, const int32_t *q_indptr, const int32_t *tree_parent,
                                    const void *target_logits, const int32_t *draft_tokens, int32_t *accepted_len,
                                    int32_t *out_tokens, int32_t *accepted_nodes, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
+ * Sampled acceptance over draft trees (Section 2.2, as above, at temperature > 0).  Tree layout as for
+ * ss_spec_accept_tree_greedy; draft row i-1 of the request (row q_indptr[b]-b+i-1 of draft_logits) is the
+ * distribution node i's token was drawn from (siblings drawn from one proposal carry equal rows), and
+ * u_accept at the same index is its uniform.  The walk starts at node 0 with r = softmax(target row 0 / T)
+ * and offers r the children of the current node in node order, each as one step of speculative sampling
+ * against its own proposal q_c = softmax(draft row of c / T):
+ *     accept c iff u_c * q_c[x_c] < r[x_c]; then c is the current node, r = softmax(target row c / T)
+ *     rejected: r <- max(0, r - q_c) / sum(max(0, r - q_c))  (unchanged if that sum is 0); next sibling
+ *     no child left: y = first token whose running sum of r (token order) exceeds u_sample_b * sum(r); if the
+ *     last rejection left no residual mass, y = lowest-index argmax of the current node's target row
+ * Every step leaves the distribution that plain sampling from the target would have at that point, so the
+ * emitted tokens are distributed as the target's own; a chain gives the result of ss_spec_accept.
+ *   out_tokens, accepted_len, accepted_nodes   as for ss_spec_accept_tree_greedy
+ *   ratio_out   device float [total_rows-batch] or NULL: r[x]/q[x] of every node that was offered, NaN elsewhere
+ *   workspace   >= ss_spec_accept_tree_sample_workspace(...) bytes (it holds three fp64 vocabulary vectors
+ *               per request besides the row statistics)
+ * All arithmetic after the row maxima is fp64 with fixed reduction orders.  This call favours exactness
+ * over speed: each request is walked by one workgroup, one vocabulary sweep per offered and per accepted
+ * node.  Other arguments and errors as for ss_spec_accept.
+ */
+size_t ss_spec_accept_tree_sample_workspace(int32_t batch, int32_t total_rows, int32_t vocab);
+int32_t ss_spec_accept_tree_sample(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
+                                   int32_t total_rows, int32_t max_q_len, const int32_t *q_indptr,
+                                   const int32_t *tree_parent, const void *target_logits, const void *draft_logits,
+                                   const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                                   const float *temperature, float temperature_scalar, int32_t *accepted_len,
+                                   int32_t *out_tokens, int32_t *accepted_nodes, float *ratio_out, void *workspace,
                                    size_t workspace_bytes, void *stream);
 
 /*

@@ -22,7 +22,8 @@ SS_OUT_WIDTH = SS_MAX_DEPTH + 1
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_kv_append", "ss_kv_compact", "ss_kv_commit", "ss_depth_init",
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_spec_accept_tree_sample_workspace",
+           "ss_spec_accept_tree_sample", "ss_kv_append", "ss_kv_compact", "ss_kv_commit", "ss_depth_init",
            "ss_depth_update", "ss_route_select", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
 
@@ -95,6 +96,12 @@ def lib() -> ctypes.CDLL:
         L.ss_kv_append.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
                                    ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         L.ss_kv_commit.restype = ctypes.c_int32
+        L.ss_spec_accept_tree_sample_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.ss_spec_accept_tree_sample_workspace.restype = ctypes.c_size_t
+        L.ss_spec_accept_tree_sample.argtypes = ([ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_int32] + [ctypes.c_void_p] * 8 + [ctypes.c_float] +
+                                                 [ctypes.c_void_p] * 5 + [ctypes.c_size_t, ctypes.c_void_p])
+        L.ss_spec_accept_tree_sample.restype = ctypes.c_int32
         L.ss_kv_compact.argtypes = [ctypes.POINTER(ss_paged_kv), ctypes.POINTER(ss_batch), ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
         L.ss_kv_compact.restype = ctypes.c_int32
@@ -306,6 +313,25 @@ def ss_spec_accept_tree_greedy(d: Dict[str, object], accepted_len: torch.Tensor,
                                             _ptr(d["target_logits"]), _ptr(d["draft_tokens"]), _ptr(accepted_len),
                                             _ptr(out_tokens), _ptr(accepted_nodes), _ptr(workspace),
                                             workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ss_spec_accept_tree_sample(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,
+                               accepted_nodes: torch.Tensor, ratio_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                               max_q_len: int = 0) -> None:
+    _check(lib().ss_spec_accept_tree_sample(d["batch"], d["vocab"], d["row_stride"], _DT[d["logit_dtype"]],
+                                            d["total_rows"], max_q_len, _ptr(d["q_indptr"]), _ptr(d["tree_parent"]),
+                                            _ptr(d["target_logits"]), _ptr(d["draft_logits"]), _ptr(d["draft_tokens"]),
+                                            _ptr(d["u_accept"]), _ptr(d["u_sample"]), _ptr(d["temperature"]),
+                                            ctypes.c_float(0.0), _ptr(accepted_len), _ptr(out_tokens),
+                                            _ptr(accepted_nodes), _ptr(ratio_out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream()))
+
+
+def tree_sample_workspace(d: Dict[str, object], device="cuda:0") -> torch.Tensor:
+    n = lib().ss_spec_accept_tree_sample_workspace(d["batch"], d["total_rows"], d["vocab"])
+    if n == 0 and d["batch"] > 0:
+        raise SpecVerifyError(lib().ss_last_error().decode())
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
 
 
 def alloc_accept_outputs(d: Dict[str, object], device="cuda:0"):

@@ -394,6 +394,44 @@ def make_tree_accept_inputs(cfg: VerifyConfig, seed: int = 0, *, depth: Optional
     return inp
 
 
+def make_tree_sample_inputs(cfg: VerifyConfig, seed: int = 0, *, depth: Optional[np.ndarray] = None,
+                            row_pad: int = 0) -> Dict[str, object]:
+    """A batch for sampled acceptance over draft trees.
+
+    Target logits, uniforms, temperatures and sizes are those of ``make_accept_inputs``; the drafts of a
+    request form the random tree of ``draw_draft_trees``.  The children of a node are drawn, as a draft
+    model would, from one proposal: the node's target row plus N(0, sigma_draft) noise (one noise
+    vector per parent), rounded to the logit dtype; draft row i-1 holds the proposal node i was drawn
+    from, so siblings carry equal rows.
+    """
+    inp = make_accept_inputs(cfg, seed, depth=depth, row_pad=row_pad)
+    q_indptr, V, stride = inp["q_indptr"], inp["vocab"], inp["row_stride"]
+    B = inp["batch"]
+    parent, mask = draw_draft_trees(q_indptr, _rng(cfg, seed, 10))
+    rn = _rng(cfg, seed, 12)
+    tgt = decode_storage(inp["target_logits"], cfg.logit_dtype)
+    Rd = inp["total_rows"] - B
+    drf = np.empty((max(Rd, 1), stride), dtype=np.float32)
+    drf[:, V:] = np.float32(3.0e4)
+    for b in range(B):
+        r0, n = int(q_indptr[b]), int(q_indptr[b + 1] - q_indptr[b])
+        proposal = {}
+        for i in range(1, n):
+            p = int(parent[r0 + i])
+            if p not in proposal:
+                noise = rn.standard_normal(V, dtype=np.float32) * np.float32(inp["sigma_draft"][b])
+                proposal[p] = tgt[r0 + p, :V] + noise
+            drf[r0 - b + i - 1, :V] = proposal[p]
+    drf = drf[:Rd] if Rd > 0 else drf[:0]
+    drf_s = store(drf, cfg.logit_dtype)
+    drf_val = decode_storage(drf_s, cfg.logit_dtype)[:, :V] if Rd > 0 else np.zeros((0, V), np.float32)
+    row_T = np.repeat(inp["temperature"], inp["depth"])
+    inp["draft_logits"] = drf_s
+    inp["draft_tokens"] = _sample_rows_inverse_cdf(drf_val, row_T, _rng(cfg, seed, 6).random(Rd))
+    inp["tree_parent"], inp["tree_mask"] = parent, mask
+    return inp
+
+
 def decode_storage(x: np.ndarray, dtype: str) -> np.ndarray:
     """Storage -> float32 via torch (generator-side helper for drawing draft tokens and for tests)."""
     if dtype == "f32":
