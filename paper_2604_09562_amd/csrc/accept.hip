@@ -823,11 +823,13 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
 // One 1024-lane workgroup per request walks its tree on its own, in fp64: the current distribution r
 // lives unnormalised in device memory (value / norm), every child is offered against it with the exact
 // ratio r[x]/q[x], a rejection replaces r by the normalised residual max(0, r - q) (written to the
-// second buffer, which then becomes current), an acceptance reloads r from the accepted node's target
-// row, and the last token is drawn by the inverse CDF over r.  Every step sweeps the vocabulary with the
-// workgroup's lanes and reduces in a fixed order, so the result is run-to-run identical.  The row maxima
-// come from the row-statistics pass.  This path favours exactness over speed: a request costs one
-// vocabulary sweep per offered child plus one per accepted child, all on one compute unit.
+// second buffer, which then becomes current), an acceptance moves on to the accepted node's target
+// distribution, and the last token is drawn by the inverse CDF over r.  While r is still a node's own
+// target distribution it is not written out: a child is judged from two gathered logits and the row
+// statistics of the first pass, and only a rejection (or the final draw) sweeps the vocabulary.  Sweeps
+// use the workgroup's lanes and reduce in a fixed order, so the result is run-to-run identical.  This
+// path favours exactness over speed: a request costs two or three vocabulary sweeps per rejected
+// child and one or two for the draw, all on one compute unit.
 constexpr int kTreeThreads = 1024;
 
 struct TreeShared {
@@ -875,15 +877,20 @@ __global__ __launch_bounds__(kTreeThreads) void accept_tree_sample_kernel(Accept
     double *cur_arr = buf + (int64_t)b * 3 * V, *alt = cur_arr + V, *eq = cur_arr + 2 * (int64_t)V;
     double norm = 1.0;
 
-    // maximum of a row from the chunk maxima of the row-statistics pass (every lane computes it)
-    auto row_max = [&](int64_t ry) {
-        float m = -INFINITY;
+    // Maximum and normaliser of a row from the chunk statistics of the row-statistics pass (every lane
+    // computes them).  The maximum is exact; the normaliser carries the fp32 rounding of the chunk sums
+    // (relative error below 1e-6) and is only used to judge a child, never in a residual.
+    auto row_stats = [&](int64_t ry, float &m, double &z) {
+        m = -INFINITY;
         for (int c = 0; c < w.nchunks; ++c) m = fmaxf(m, w.cmax[ry * w.nchunks + c]);
-        return m;
+        z = 0.0;
+        for (int c = 0; c < w.nchunks; ++c) {
+            const float cm = w.cmax[ry * w.nchunks + c];
+            if (cm != -INFINITY) z += (double)w.csum[ry * w.nchunks + c] * exp2(((double)cm - (double)m) * inv_t * kLog2eD);
+        }
     };
-    // r <- softmax of a target row (unnormalised exponentials in cur_arr, their sum in norm)
-    auto load_target = [&](int node) {
-        const float m = row_max((int64_t)t0 + node);
+    // cur_arr <- exponentials of a target row, norm <- their exact sum: r = softmax of the row
+    auto materialise = [&](int node, float m) {
         double s = 0.0;
         for (int v = tid; v < V; v += kTreeThreads) {
             const double e = ex(((double)load_logit(a.target, t0 + node, a.row_stride, DT, v) - (double)m) * inv_t);
@@ -896,22 +903,22 @@ __global__ __launch_bounds__(kTreeThreads) void accept_tree_sample_kernel(Accept
     if (tid < k && a.ratio_out) a.ratio_out[d0 + tid] = __builtin_nanf("");
     int cur = 0, n = 0, my_tok = -1, my_node = -1;
     bool degenerate = false;
-    load_target(0);
+    bool pure = true;   // r is still the current node's own target distribution and has not been written out
+    float mp;
+    double zp;
+    row_stats(t0, mp, zp);
     for (;;) {
         bool moved = false;
         for (int c = cur + 1; c <= k && !moved; ++c) {
             if (a.tree_parent[t0 + c] != cur) continue;
             const int x = a.draft_tokens[d0 + c - 1];
             const double u = (double)a.u_accept[d0 + c - 1];
-            const float mq = row_max((int64_t)a.total_rows + d0 + c - 1);
-            double s = 0.0;
-            for (int v = tid; v < V; v += kTreeThreads) {
-                const double e = ex(((double)load_logit(a.draft, d0 + c - 1, a.row_stride, DT, v) - (double)mq) * inv_t);
-                eq[v] = e;
-                s += e;
-            }
-            const double zq = tree_sum(s, sh);
-            const double rx = cur_arr[x] / norm, qx = eq[x] / zq;
+            float mq;
+            double zq;
+            row_stats((int64_t)a.total_rows + d0 + c - 1, mq, zq);
+            const double qx = ex(((double)load_logit(a.draft, d0 + c - 1, a.row_stride, DT, x) - (double)mq) * inv_t) / zq;
+            const double rx = pure ? ex(((double)load_logit(a.target, t0 + cur, a.row_stride, DT, x) - (double)mp) * inv_t) / zp
+                                   : cur_arr[x] / norm;
             if (tid == 0 && a.ratio_out) a.ratio_out[d0 + c - 1] = (float)(rx / qx);
             if (u * qx < rx) {
                 if (tid == n) {
@@ -921,13 +928,26 @@ __global__ __launch_bounds__(kTreeThreads) void accept_tree_sample_kernel(Accept
                 ++n;
                 cur = c;
                 degenerate = false;
-                __syncthreads();   // everyone has read cur_arr[x] before it is overwritten
-                load_target(c);
+                pure = true;
+                row_stats((int64_t)t0 + c, mp, zp);
                 moved = true;
             } else {
+                // the residual is taken exactly: both distributions with their fp64 normalisers
+                __syncthreads();   // (lanes may still be reading cur_arr[x])
+                if (pure) {
+                    materialise(cur, mp);
+                    pure = false;
+                }
+                double s = 0.0;
+                for (int v = tid; v < V; v += kTreeThreads) {
+                    const double e = ex(((double)load_logit(a.draft, d0 + c - 1, a.row_stride, DT, v) - (double)mq) * inv_t);
+                    eq[v] = e;
+                    s += e;
+                }
+                const double zq_exact = tree_sum(s, sh);
                 double sr = 0.0;
                 for (int v = tid; v < V; v += kTreeThreads) {
-                    const double rt = cur_arr[v] / norm, qt = eq[v] / zq;
+                    const double rt = cur_arr[v] / norm, qt = eq[v] / zq_exact;
                     const double res = rt > qt ? rt - qt : 0.0;
                     alt[v] = res;
                     sr += res;
@@ -947,12 +967,15 @@ __global__ __launch_bounds__(kTreeThreads) void accept_tree_sample_kernel(Accept
 
     int y;
     if (degenerate) {   // the residual vanished: lowest-index maximum of the current node's target row
-        const float m = row_max((int64_t)t0 + cur);
+        float m;
+        double z;
+        row_stats((int64_t)t0 + cur, m, z);
         int best = 0x7fffffff;
         for (int v = tid; v < V; v += kTreeThreads)
             if (load_logit(a.target, t0 + cur, a.row_stride, DT, v) == m) { best = v; break; }
         y = tree_min(best, sh);
     } else {
+        if (pure) materialise(cur, mp);
         // inverse CDF in token order: lane t owns the contiguous entries [t*seg, (t+1)*seg)
         const int seg = (V + kTreeThreads - 1) / kTreeThreads;
         const int lo = min(V, tid * seg), hi = min(V, lo + seg);
