@@ -11,7 +11,7 @@ for by seeded random tensors, there being no weights here):
   attention   verify attention, once per layer; layers after the first        ss_spec_verify_attn
               reuse the first one's plan                                      (SS_BATCH_REUSE_PLAN)
   accept      acceptance walk and the draw of the next token                  ss_spec_accept, or for draft trees
-                                                                              ss_spec_accept_tree_greedy + ss_kv_compact
+                                                                              ss_spec_accept_tree_greedy / _sample + ss_kv_compact
   commit      new valid lengths                                               ss_kv_commit
 
 and prints the accepted tokens per step.  Every device step runs in the library's kernels; this file
@@ -29,7 +29,7 @@ from . import binding, synth
 
 
 def run(steps: int = 6, batch: int = 8, layers: int = 4, tree: bool = False, vocab: int = 32000, seed: int = 0,
-        verbose: bool = True) -> dict:
+        verbose: bool = True, sample: bool = False) -> dict:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[1].scaled(batch=batch, vocab=vocab, ctx=("uniform", 200, 1500))
@@ -54,7 +54,9 @@ def run(steps: int = 6, batch: int = 8, layers: int = 4, tree: bool = False, voc
 
     for step in range(steps):
         # ---- what the models would hand over: draft tokens/logits, queries and new keys/values per layer
-        if tree:
+        if tree and sample:
+            acc = synth.make_tree_sample_inputs(cfg, seed=seed + step, depth=depth)
+        elif tree:
             acc = synth.make_tree_accept_inputs(cfg, seed=seed + step, depth=depth, hit=0.7)
         else:
             acc = synth.make_accept_inputs(cfg, seed=seed + step, depth=depth)
@@ -71,6 +73,7 @@ def run(steps: int = 6, batch: int = 8, layers: int = 4, tree: bool = False, voc
         out, lse, ws = binding.alloc_attention_outputs(d, dev, max_q_len=mq)
         n_acc, toks, _, ws_a = binding.alloc_accept_outputs(da, dev)
         nodes = torch.empty((batch, binding.SS_MAX_DEPTH), dtype=torch.int32, device=dev)
+        ws_t = binding.tree_sample_workspace(da, dev) if tree and sample else None
 
         # ---- the device side of the step
         torch.cuda.synchronize()
@@ -79,7 +82,10 @@ def run(steps: int = 6, batch: int = 8, layers: int = 4, tree: bool = False, voc
         for layer in range(layers):   # one cache stands in for every layer's; the batch metadata is shared
             binding.ss_spec_verify_attn(d, out, lse, ws, max_q_len=mq, reuse_plan=layer > 0)
         if tree:
-            binding.ss_spec_accept_tree_greedy(da, n_acc, toks, nodes, ws_a, max_q_len=mq)
+            if sample:
+                binding.ss_spec_accept_tree_sample(da, n_acc, toks, nodes, None, ws_t, max_q_len=mq)
+            else:
+                binding.ss_spec_accept_tree_greedy(da, n_acc, toks, nodes, ws_a, max_q_len=mq)
             binding.ss_kv_compact(d, nodes, n_acc, max_q_len=mq)
         else:
             binding.ss_spec_accept(da, n_acc, toks, None, ws_a, max_q_len=mq)
@@ -108,9 +114,10 @@ def main() -> None:
     ap.add_argument("--steps", type=int, default=6)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--layers", type=int, default=4)
-    ap.add_argument("--tree", action="store_true", help="tree-shaped drafts with greedy acceptance")
+    ap.add_argument("--tree", action="store_true", help="tree-shaped drafts (greedy acceptance unless --sample)")
+    ap.add_argument("--sample", action="store_true", help="with --tree: the sampled acceptance walk")
     a = ap.parse_args()
-    run(a.steps, a.batch, a.layers, a.tree)
+    run(a.steps, a.batch, a.layers, a.tree, sample=a.sample)
 
 
 if __name__ == "__main__":

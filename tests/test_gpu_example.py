@@ -7,9 +7,9 @@ from paper_2604_09562_amd import example
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("tree", [False, True], ids=["chain", "tree"])
-def test_example_decode_lane(tree):
-    r = example.run(steps=4, batch=5, layers=3, tree=tree, vocab=4096, seed=3, verbose=False)
+@pytest.mark.parametrize("tree,sample", [(False, False), (True, False), (True, True)], ids=["chain", "tree", "tree_sampled"])
+def test_example_decode_lane(tree, sample):
+    r = example.run(steps=4, batch=5, layers=3, tree=tree, vocab=4096, seed=3, verbose=False, sample=sample)
     assert 0 <= r["chosen"] < 4
     assert r["emitted"] >= 4 * 5                       # every request emits at least one token per step
     # every emitted token but the one still in flight has become a valid cache position

@@ -9,6 +9,7 @@ from paper_2604_09562_amd import binding, synth
 from tests.test_gpu_attn import check
 from tests.test_gpu_accept import compare as compare_accept
 from tests.test_gpu_kv import run_and_compare as append_and_compare
+from tests.test_gpu_tree_sample import compare as compare_tree_sample
 from tests.test_oracle_kv_compact import random_paths
 
 pytestmark = pytest.mark.gpu
@@ -54,6 +55,9 @@ def test_random_shape(oracle, case):
         assert np.array_equal(n_acc.cpu().numpy(), ref["accepted_len"]), label
         assert np.array_equal(toks.cpu().numpy(), ref["out_tokens"]), label
         assert np.array_equal(nodes.cpu().numpy(), ref["accepted_nodes"]), label
+        if case % 2:   # the sampled walk over the same trees
+            compare_tree_sample(synth.make_tree_sample_inputs(cfg, seed=case, depth=depth, row_pad=pad), oracle,
+                                label + " sampled walk", max_q_len=mq)
         # compaction of a random root path (deeper than the greedy walk usually gets)
         path_nodes, path_len = random_paths(app, case)
         d = binding.attention_to_device(app)
