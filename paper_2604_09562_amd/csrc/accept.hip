@@ -17,208 +17,10 @@
 // inside the block that holds u * mass.
 // All reductions have a fixed order (no atomics): results are run-to-run identical.
 #include "common.h"
+#include "accept_common.h"
 
 namespace ss {
 namespace {
-
-constexpr int kThreads = 256;
-constexpr int kSub = 2048;                     // vocabulary entries per workgroup in the fp64 passes
-constexpr int kSubPer = kSub / kThreads;       // 8 logits per lane there
-constexpr int kMaxRows = 2 * SS_MAX_DEPTH + 1; // rows of one request: k+1 target, k draft
-constexpr double kLog2eD = 1.4426950408889634;
-
-struct RowPick {      // written by decide, read by the resampling passes
-    int32_t p_row;    // target row the new token is drawn from
-    int32_t q_row;    // draft row of the rejected position, -1 if every draft was accepted
-    float m_p, m_q;   // exact row maxima
-    float temperature;
-    int32_t n;        // accepted length
-    double rho;       // Zp/Zq as known from the fp32 row statistics (relative error below 2e-5)
-};
-
-constexpr int kAmbCap = 4096;       // listed boundary entries per request; beyond that the slow exact path runs
-constexpr double kAmbEps = 1.0e-4;  // relative half-width of the boundary zone around p == q
-constexpr int kPickWgs = 8;         // workgroups per request in the last pass (all but one idle unless the list overflowed)
-
-struct Workspace {
-    float *cmax, *csum;   // [rows][nchunks]
-    int32_t *carg;        // [rows][nchunks]
-    RowPick *pick;        // [batch]
-    double *zp, *zq, *sc; // [batch][nsub]: sums of exp over all entries of the block (p row, q row), block mass
-    double *pp, *qq;      // [batch][nsub]: the same sums over the entries with p clearly above q
-    int32_t *amb_cnt;     // [batch] entries in the boundary zone (may exceed kAmbCap: then the list is not used)
-    int32_t *done;        // [batch] workgroups of the last pass that have delivered their block masses
-    int32_t *blk_base, *blk_cnt;  // [batch][nsub] where in the list a block's entries start, and how many they are
-    double *amb_ep, *amb_eq;  // [batch][kAmbCap] their unnormalised exponentials, each block's entries contiguous
-    int nchunks, nsub, rows;
-};
-
-__host__ __device__ inline int num_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
-__host__ __device__ inline int num_sub(int vocab) { return (vocab + kSub - 1) / kSub; }
-
-__host__ Workspace carve(void *ws, int batch, int total_rows, int vocab)
-{
-    Workspace w;
-    w.nchunks = num_chunks(vocab);
-    w.nsub = num_sub(vocab);
-    w.rows = 2 * total_rows - batch;
-    char *p = static_cast<char *>(ws);
-    const size_t per = align_up(sizeof(float) * (size_t)w.rows * w.nchunks, 256);
-    w.cmax = reinterpret_cast<float *>(p); p += per;
-    w.csum = reinterpret_cast<float *>(p); p += per;
-    w.carg = reinterpret_cast<int32_t *>(p); p += per;
-    w.pick = reinterpret_cast<RowPick *>(p); p += align_up(sizeof(RowPick) * (size_t)batch, 256);
-    const size_t perd = align_up(sizeof(double) * (size_t)batch * w.nsub, 256);
-    w.zp = reinterpret_cast<double *>(p); p += perd;
-    w.zq = reinterpret_cast<double *>(p); p += perd;
-    w.sc = reinterpret_cast<double *>(p); p += perd;
-    w.pp = reinterpret_cast<double *>(p); p += perd;
-    w.qq = reinterpret_cast<double *>(p); p += perd;
-    const size_t pera = align_up(sizeof(double) * (size_t)batch * kAmbCap, 256);
-    w.amb_ep = reinterpret_cast<double *>(p); p += pera;
-    w.amb_eq = reinterpret_cast<double *>(p); p += pera;
-    const size_t peri = align_up(sizeof(int32_t) * (size_t)batch * w.nsub, 256);
-    w.blk_base = reinterpret_cast<int32_t *>(p); p += peri;
-    w.blk_cnt = reinterpret_cast<int32_t *>(p); p += peri;
-    w.amb_cnt = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch, 256);
-    w.done = reinterpret_cast<int32_t *>(p); p += align_up(sizeof(int32_t) * (size_t)batch, 256);
-    return w;
-}
-
-// ---- loading one lane's share of a block of N*256 vocabulary entries -------------------------
-// Coalesced order: lane t owns entries base + it*(256*vec) + t*vec + j (vec = 8 for bf16, 4 for f32).
-// Sequential order (the inverse-CDF search): lane t owns base + t*N .. + N-1.
-// Out-of-vocabulary positions read as -inf.  index_of() gives the vocabulary id of slot s.
-// DT is the logit dtype (SS_BF16 or SS_F32): the kernels are compiled once per dtype.
-template <int DT, int N, bool SEQ>
-__device__ __forceinline__ int index_of(int base, int tid, int s)
-{
-    if (SEQ) return base + tid * N + s;
-    constexpr int vec = DT == SS_BF16 ? 8 : 4;
-    return base + (s / vec) * (kThreads * vec) + tid * vec + (s % vec);
-}
-
-template <int DT, int N, bool SEQ>
-__device__ __forceinline__ void load_slots(const void *row, int vocab, int base, int tid, float (&x)[N])
-{
-    constexpr int vec = DT == SS_BF16 ? 8 : 4;
-    if (base + N * kThreads <= vocab) {   // whole block inside the vocabulary (uniform): plain 16-byte loads
-        uint4 w[N / vec];
-#pragma unroll
-        for (int it = 0; it < N / vec; ++it) {
-            const int i0 = index_of<DT, N, SEQ>(base, tid, it * vec);
-            if constexpr (DT == SS_BF16)
-                w[it] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + i0);
-            else
-                w[it] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(row) + i0);
-        }
-#pragma unroll
-        for (int it = 0; it < N / vec; ++it) {
-            const uint32_t ww[4] = {w[it].x, w[it].y, w[it].z, w[it].w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if constexpr (DT == SS_BF16) {
-                    x[it * 8 + 2 * j] = __uint_as_float(ww[j] << 16);
-                    x[it * 8 + 2 * j + 1] = __uint_as_float(ww[j] & 0xffff0000u);
-                } else {
-                    x[it * 4 + j] = __uint_as_float(ww[j]);
-                }
-            }
-        }
-        return;
-    }
-    // The block that holds the end of the vocabulary.  Every lane still issues 16-byte loads (from a
-    // clamped, in-bounds address, so that they pipeline); lanes whose vector lies past the end drop
-    // the data, and the one vector that straddles the end is read element by element.
-    const int last_full = vocab >= vec ? (vocab - vec) / vec * vec : -1;
-#pragma unroll
-    for (int it = 0; it < N / vec; ++it) {
-        const int i0 = index_of<DT, N, SEQ>(base, tid, it * vec);
-        uint4 w = make_uint4(0, 0, 0, 0);
-        if (last_full >= 0) {
-            const int ic = i0 < last_full ? i0 : last_full;
-            if constexpr (DT == SS_BF16)
-                w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(row) + ic);
-            else
-                w = *reinterpret_cast<const uint4 *>(static_cast<const float *>(row) + ic);
-        }
-        const bool whole = i0 + vec <= vocab;
-        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if constexpr (DT == SS_BF16) {
-                x[it * 8 + 2 * j] = whole ? __uint_as_float(ww[j] << 16) : -INFINITY;
-                x[it * 8 + 2 * j + 1] = whole ? __uint_as_float(ww[j] & 0xffff0000u) : -INFINITY;
-            } else {
-                x[it * 4 + j] = whole ? __uint_as_float(ww[j]) : -INFINITY;
-            }
-        }
-        if (!whole && i0 < vocab) {
-#pragma unroll
-            for (int j = 0; j < vec; ++j) {
-                if (i0 + j < vocab) {
-                    if constexpr (DT == SS_BF16)
-                        x[it * vec + j] = __uint_as_float((uint32_t) static_cast<const uint16_t *>(row)[i0 + j] << 16);
-                    else
-                        x[it * vec + j] = static_cast<const float *>(row)[i0 + j];
-                }
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ const void *row_ptr(const void *base, int64_t row, int64_t stride, int dtype)
-{
-    return static_cast<const char *>(base) + row * stride * (dtype == SS_BF16 ? 2 : 4);
-}
-
-__device__ __forceinline__ float load_logit(const void *base, int64_t row, int64_t stride, int dtype, int v)
-{
-    const void *r = row_ptr(base, row, stride, dtype);
-    if (dtype == SS_BF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(r)[v] << 16);
-    return static_cast<const float *>(r)[v];
-}
-
-// ---- block reductions with a fixed order ---------------------------------------------------
-__device__ __forceinline__ float block_max(float v, float *sh)
-{
-    for (int off = 32; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
-}
-template <typename T>
-__device__ __forceinline__ T block_sum(T v, T *sh)
-{
-    for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return (sh[0] + sh[1]) + (sh[2] + sh[3]);
-}
-
-// ---- fp64 exponential for non-positive arguments -----------------------------------------------
-// exp(x) = 2^e * 2^(j/64) * exp(r), x = (64 e + j) ln2/64 + r, |r| <= ln2/128, with a 64-entry
-// table of 2^(j/64) in LDS and a degree-5 Taylor polynomial (remainder < 4e-17 relative).
-struct ExpTable {
-    double t[64];
-    __device__ void init()
-    {
-        if (threadIdx.x < 64) t[threadIdx.x] = exp2((double)threadIdx.x * (1.0 / 64.0));
-        __syncthreads();
-    }
-    __device__ __forceinline__ double operator()(double x) const
-    {
-        x = fmax(x, -746.0);   // exp underflows to 0 from there on (also covers -inf)
-        const double kd = rint(x * 92.33248261689366);  // 64 / ln 2
-        double r = fma(kd, -0x1.62e42fee00000p-7, x);    // ln2/64: high part with 21 trailing zero bits
-        r = fma(kd, -0x1.a39ef35793c76p-39, r);          //         low part
-        const int k = (int)kd;
-        const double p = fma(fma(fma(fma(fma(r, 1.0 / 120.0, 1.0 / 24.0), r, 1.0 / 6.0), r, 0.5), r, 1.0), r, 1.0);
-        return ldexp(t[k & 63] * p, k >> 6);
-    }
-};
 
 // ---- pass 1 ---------------------------------------------------------------------------------
 // grid: batch * rows_max * ceil(nchunks / 4), rows_max from the caller's bound of k+1; workgroup (b, j, group): wave wv of it streams chunk
@@ -819,212 +621,6 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(AcceptArgs a, Wor
     }
 }
 
-// ---- sampled acceptance over a draft tree ------------------------------------------------------------------
-// One 1024-lane workgroup per request walks its tree on its own, in fp64: the current distribution r
-// lives unnormalised in device memory (value / norm), every child is offered against it with the exact
-// ratio r[x]/q[x], a rejection replaces r by the normalised residual max(0, r - q) (written to the
-// second buffer, which then becomes current), an acceptance moves on to the accepted node's target
-// distribution, and the last token is drawn by the inverse CDF over r.  While r is still a node's own
-// target distribution it is not written out: a child is judged from two gathered logits and the row
-// statistics of the first pass, and only a rejection (or the final draw) sweeps the vocabulary.  Sweeps
-// use the workgroup's lanes and reduce in a fixed order, so the result is run-to-run identical.  This
-// path favours exactness over speed: a request costs two or three vocabulary sweeps per rejected
-// child and one or two for the draw, all on one compute unit.
-constexpr int kTreeThreads = 1024;
-
-struct TreeShared {
-    double red[kTreeThreads / 64];
-    int ired[kTreeThreads / 64];
-};
-
-__device__ __forceinline__ double tree_sum(double v, TreeShared &sh)
-{
-    for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh.red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double s = 0.0;
-#pragma unroll
-    for (int i = 0; i < kTreeThreads / 64; ++i) s += sh.red[i];
-    return s;
-}
-
-__device__ __forceinline__ int tree_min(int v, TreeShared &sh)
-{
-    for (int off = 32; off; off >>= 1) v = min(v, __shfl_xor(v, off));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh.ired[threadIdx.x >> 6] = v;
-    __syncthreads();
-    int s = 0x7fffffff;
-#pragma unroll
-    for (int i = 0; i < kTreeThreads / 64; ++i) s = min(s, sh.ired[i]);
-    return s;
-}
-
-__device__ __forceinline__ int tree_max(int v, TreeShared &sh) { return -tree_min(-v, sh); }
-
-template <int DT>
-__global__ __launch_bounds__(kTreeThreads) void accept_tree_sample_kernel(AcceptArgs a, Workspace w, double *buf)
-{
-    __shared__ ExpTable ex;
-    __shared__ TreeShared sh;
-    ex.init();
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int V = a.vocab;
-    const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1, d0 = t0 - b;
-    const float T = a.temperature ? a.temperature[b] : a.temperature_scalar;
-    const double inv_t = 1.0 / (double)T;
-    double *cur_arr = buf + (int64_t)b * 3 * V, *alt = cur_arr + V, *eq = cur_arr + 2 * (int64_t)V;
-    double norm = 1.0;
-
-    // Maximum and normaliser of a row from the chunk statistics of the row-statistics pass (every lane
-    // computes them).  The maximum is exact; the normaliser carries the fp32 rounding of the chunk sums
-    // (relative error below 1e-6) and is only used to judge a child, never in a residual.
-    auto row_stats = [&](int64_t ry, float &m, double &z) {
-        m = -INFINITY;
-        for (int c = 0; c < w.nchunks; ++c) m = fmaxf(m, w.cmax[ry * w.nchunks + c]);
-        z = 0.0;
-        for (int c = 0; c < w.nchunks; ++c) {
-            const float cm = w.cmax[ry * w.nchunks + c];
-            if (cm != -INFINITY) z += (double)w.csum[ry * w.nchunks + c] * exp2(((double)cm - (double)m) * inv_t * kLog2eD);
-        }
-    };
-    // cur_arr <- exponentials of a target row, norm <- their exact sum: r = softmax of the row
-    auto materialise = [&](int node, float m) {
-        double s = 0.0;
-        for (int v = tid; v < V; v += kTreeThreads) {
-            const double e = ex(((double)load_logit(a.target, t0 + node, a.row_stride, DT, v) - (double)m) * inv_t);
-            cur_arr[v] = e;
-            s += e;
-        }
-        norm = tree_sum(s, sh);   // (its barriers also publish cur_arr to the workgroup)
-    };
-
-    if (tid < k && a.ratio_out) a.ratio_out[d0 + tid] = __builtin_nanf("");
-    int cur = 0, n = 0, my_tok = -1, my_node = -1;
-    bool degenerate = false;
-    bool pure = true;   // r is still the current node's own target distribution and has not been written out
-    float mp;
-    double zp;
-    row_stats(t0, mp, zp);
-    for (;;) {
-        bool moved = false;
-        for (int c = cur + 1; c <= k && !moved; ++c) {
-            if (a.tree_parent[t0 + c] != cur) continue;
-            const int x = a.draft_tokens[d0 + c - 1];
-            const double u = (double)a.u_accept[d0 + c - 1];
-            float mq;
-            double zq;
-            row_stats((int64_t)a.total_rows + d0 + c - 1, mq, zq);
-            const double qx = ex(((double)load_logit(a.draft, d0 + c - 1, a.row_stride, DT, x) - (double)mq) * inv_t) / zq;
-            const double rx = pure ? ex(((double)load_logit(a.target, t0 + cur, a.row_stride, DT, x) - (double)mp) * inv_t) / zp
-                                   : cur_arr[x] / norm;
-            if (tid == 0 && a.ratio_out) a.ratio_out[d0 + c - 1] = (float)(rx / qx);
-            if (u * qx < rx) {
-                if (tid == n) {
-                    my_tok = x;
-                    my_node = c;
-                }
-                ++n;
-                cur = c;
-                degenerate = false;
-                pure = true;
-                row_stats((int64_t)t0 + c, mp, zp);
-                moved = true;
-            } else {
-                // the residual is taken exactly: both distributions with their fp64 normalisers
-                __syncthreads();   // (lanes may still be reading cur_arr[x])
-                if (pure) {
-                    materialise(cur, mp);
-                    pure = false;
-                }
-                double s = 0.0;
-                for (int v = tid; v < V; v += kTreeThreads) {
-                    const double e = ex(((double)load_logit(a.draft, d0 + c - 1, a.row_stride, DT, v) - (double)mq) * inv_t);
-                    eq[v] = e;
-                    s += e;
-                }
-                const double zq_exact = tree_sum(s, sh);
-                double sr = 0.0;
-                for (int v = tid; v < V; v += kTreeThreads) {
-                    const double rt = cur_arr[v] / norm, qt = eq[v] / zq_exact;
-                    const double res = rt > qt ? rt - qt : 0.0;
-                    alt[v] = res;
-                    sr += res;
-                }
-                const double S = tree_sum(sr, sh);
-                degenerate = !(S > 0.0);
-                if (!degenerate) {
-                    double *t = cur_arr;
-                    cur_arr = alt;
-                    alt = t;
-                    norm = S;
-                }
-            }
-        }
-        if (!moved) break;
-    }
-
-    int y;
-    if (degenerate) {   // the residual vanished: lowest-index maximum of the current node's target row
-        float m;
-        double z;
-        row_stats((int64_t)t0 + cur, m, z);
-        int best = 0x7fffffff;
-        for (int v = tid; v < V; v += kTreeThreads)
-            if (load_logit(a.target, t0 + cur, a.row_stride, DT, v) == m) { best = v; break; }
-        y = tree_min(best, sh);
-    } else {
-        if (pure) materialise(cur, mp);
-        // inverse CDF in token order: lane t owns the contiguous entries [t*seg, (t+1)*seg)
-        const int seg = (V + kTreeThreads - 1) / kTreeThreads;
-        const int lo = min(V, tid * seg), hi = min(V, lo + seg);
-        double mine = 0.0;
-        int my_last = -1;
-        for (int v = lo; v < hi; ++v) {
-            const double rt = cur_arr[v] / norm;
-            if (rt > 0.0) {
-                mine += rt;
-                my_last = v;
-            }
-        }
-        double incl = mine;
-        for (int off = 1; off < 64; off <<= 1) {
-            const double t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
-        }
-        __syncthreads();
-        if (lane == 63) sh.red[wave] = incl;
-        __syncthreads();
-        double before = 0.0, total = 0.0;
-#pragma unroll
-        for (int i = 0; i < kTreeThreads / 64; ++i) {
-            if (i < wave) before += sh.red[i];
-            total += sh.red[i];
-        }
-        const double excl = before + (incl - mine);
-        const double thr = (double)a.u_sample[b] * total;
-        const int first = tree_min(excl + mine > thr ? tid : 0x7fffffff, sh);
-        const int last_tok = tree_max(my_last, sh);
-        int tok = -1;
-        if (tid == first) {
-            double c = excl;
-            for (int v = lo; v < hi; ++v) {
-                const double rt = cur_arr[v] / norm;
-                if (rt > 0.0) {
-                    c += rt;
-                    if (tok < 0 && c > thr) tok = v;
-                }
-            }
-            if (tok < 0) tok = my_last;   // the lane total crossed but the element-wise sum rounds differently
-        }
-        y = first == 0x7fffffff ? last_tok : tree_max(tok, sh);
-    }
-    if (tid == n) my_tok = y;
-    if (tid < SS_OUT_WIDTH) a.out_tokens[(int64_t)b * SS_OUT_WIDTH + tid] = tid <= n ? my_tok : -1;
-    if (tid < SS_MAX_DEPTH) a.accepted_nodes[(int64_t)b * SS_MAX_DEPTH + tid] = tid < n ? my_node : -1;
-    if (tid == 0) a.accepted_len[b] = n;
-}
 
 }  // namespace
 
@@ -1068,28 +664,17 @@ int32_t accept_launch(const AcceptArgs &a, hipStream_t stream)
     return accept_launch_dt<SS_F32>(a, w, (unsigned)g1, (unsigned)g2, stream);
 }
 
-size_t accept_tree_workspace_bytes(int batch, int total_rows, int vocab)
-{
-    return accept_workspace_bytes(batch, total_rows, vocab) + align_up(sizeof(double) * 3 * (size_t)batch * vocab, 256);
-}
-
-int32_t accept_tree_sample_launch(const AcceptArgs &a, hipStream_t stream)
+int32_t accept_rowstats_launch(const AcceptArgs &a, hipStream_t stream)
 {
     const Workspace w = carve(a.workspace, a.batch, a.total_rows, a.vocab);
-    double *buf = reinterpret_cast<double *>(static_cast<char *>(a.workspace) +
-                                             accept_workspace_bytes(a.batch, a.total_rows, a.vocab));
-    const unsigned long long g1 = (unsigned long long)a.batch * (2 * a.max_q_len - 1) * ((w.nchunks + 3) / 4);
+    const unsigned long long g1 =
+        (unsigned long long)a.batch * (a.greedy ? a.max_q_len : 2 * a.max_q_len - 1) * ((w.nchunks + 3) / 4);
     if (g1 > 0x7fffffffull) return fail(SS_ERR_UNSUPPORTED, "batch * vocab too large for one launch");
-    if (a.logit_dtype == SS_BF16) {
+    if (a.logit_dtype == SS_BF16)
         hipLaunchKernelGGL(accept_rowstats_kernel<SS_BF16>, dim3((unsigned)g1), dim3(kThreads), 0, stream, a, w);
-        SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
-        hipLaunchKernelGGL(accept_tree_sample_kernel<SS_BF16>, dim3(a.batch), dim3(kTreeThreads), 0, stream, a, w, buf);
-    } else {
+    else
         hipLaunchKernelGGL(accept_rowstats_kernel<SS_F32>, dim3((unsigned)g1), dim3(kThreads), 0, stream, a, w);
-        SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
-        hipLaunchKernelGGL(accept_tree_sample_kernel<SS_F32>, dim3(a.batch), dim3(kTreeThreads), 0, stream, a, w, buf);
-    }
-    SS_HIP_CHECK(hipGetLastError(), "launch accept_tree_sample_kernel");
+    SS_HIP_CHECK(hipGetLastError(), "launch accept_rowstats_kernel");
     return SS_OK;
 }
 

@@ -120,6 +120,7 @@ struct AcceptArgs {
 };
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream);
+int32_t accept_rowstats_launch(const AcceptArgs &a, hipStream_t stream);   // the first pass alone (row maxima and sums)
 size_t accept_tree_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_tree_sample_launch(const AcceptArgs &a, hipStream_t stream);
 
