@@ -235,11 +235,13 @@ int32_t ss_spec_accept_tree_greedy(int32_t batch, int32_t vocab, int64_t row_str
  * emitted tokens are distributed as the target's own; a chain gives the result of ss_spec_accept.
  *   out_tokens, accepted_len, accepted_nodes   as for ss_spec_accept_tree_greedy
  *   ratio_out   device float [total_rows-batch] or NULL: r[x]/q[x] of every node that was offered, NaN elsewhere
- *   workspace   >= ss_spec_accept_tree_sample_workspace(...) bytes (it holds three fp64 vocabulary vectors
+ *   workspace   >= ss_spec_accept_tree_sample_workspace(...) bytes (it holds two fp64 vocabulary vectors
  *               per request besides the row statistics)
- * All arithmetic after the row maxima is fp64 with fixed reduction orders.  This call favours exactness
- * over speed: each request is walked by one workgroup, one vocabulary sweep per offered and per accepted
- * node.  Other arguments and errors as for ss_spec_accept.
+ *   max_q_len   also bounds the number of rejections a request can have, hence the number of rounds the
+ *               call enqueues (a walk, block sums and a residual pass per round): a tight bound saves launches
+ * Children are judged from two gathered logits and the row statistics (fp32 chunk sums, relative error
+ * below 1e-6, as in ss_spec_accept); residuals, their normalisers and the draw are fp64 with fixed reduction
+ * orders.  Other arguments and errors as for ss_spec_accept.
  */
 size_t ss_spec_accept_tree_sample_workspace(int32_t batch, int32_t total_rows, int32_t vocab);
 int32_t ss_spec_accept_tree_sample(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype,
