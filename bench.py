@@ -258,6 +258,24 @@ def main() -> int:
         t_app.append(ev[0].elapsed_time(ev[1]))
         t_com.append(ev[1].elapsed_time(ev[2]))
         lens.copy_(d_att[0]["kv_len"])
+    if args.tree:
+        # the acceptance calls for tree-shaped drafts on the same trees (outside the timed step, which runs the chain rule)
+        tr = synth.make_tree_sample_inputs(cfg, seed=args.seed, depth=att["depth"])
+        d_tr = binding.accept_to_device(tr, dev)
+        nodes = torch.empty((att["batch"], binding.SS_MAX_DEPTH), dtype=torch.int32, device=dev)
+        ws_tr = binding.tree_sample_workspace(d_tr, dev)
+        t_tg, t_ts = [], []
+        for i in range(6):
+            ev[0].record()
+            binding.ss_spec_accept_tree_greedy(d_tr, g_acc, g_toks, nodes, ws_acc, max_q_len=max_q_len)
+            ev[1].record()
+            binding.ss_spec_accept_tree_sample(d_tr, g_acc, g_toks, nodes, None, ws_tr, max_q_len=max_q_len)
+            ev[2].record()
+            torch.cuda.synchronize()
+            t_tg.append(ev[0].elapsed_time(ev[1]))
+            t_ts.append(ev[1].elapsed_time(ev[2]))
+        result["t_tree_accept_greedy_ms"] = float(np.median(t_tg))
+        result["t_tree_accept_sample_ms"] = float(np.median(t_ts))
     result["t_kv_append_ms"] = float(np.median(t_app))
     result["t_kv_commit_ms"] = float(np.median(t_com))
     if args.cpu_requests != 0:
