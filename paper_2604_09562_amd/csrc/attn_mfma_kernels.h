@@ -29,6 +29,7 @@
 #include <hip/hip_ext.h>
 
 #include "common.h"
+#include "tree_window.h"
 
 namespace ss {
 namespace {
@@ -356,12 +357,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if constexpr (TREE) {
-                // A 64-position window: 32 positions of old context (all visible) below the 32 mask
-                // bits of the new tokens; shifted so that bit e is this lane's position tok0 + e.
                 // Positions past the cache end are past the mask's last set bit.
-                const int sh = tok0 - ctx + 32;
-                const uint64_t window = ((uint64_t)newmask[nb] << 32) | 0xffffffffull;
-                const uint32_t vis = sh < 0 ? 0xfu : (uint32_t)(window >> (sh & 63));
+                const uint32_t vis = tree_visible4(newmask[nb], tok0 - ctx);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? s[nb][e] * kscale : -INFINITY;
             } else {

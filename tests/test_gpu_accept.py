@@ -46,6 +46,9 @@ def compare(inp, oracle, greedy=None, label="", **kw):
         assert excused, (f"{label}: request {b}: gpu n={acc[b]} tokens={toks[b].tolist()} "
                          f"oracle n={ref['accepted_len'][b]} tokens={ref['out_tokens'][b].tolist()}")
         near_ties += 1
+    # with p/q known to about 2e-6 relative, an excusal needs u within that of the ratio: a once-in-1e5 event per draft
+    n_drafts = int(inp["total_rows"] - B)
+    assert near_ties <= max(1, int(1e-4 * n_drafts)), f"{label}: {near_ties} near-tie excusals among {n_drafts} drafts"
     if not (inp["greedy"] if greedy is None else greedy):
         Rd = inp["total_rows"] - B
         if Rd:
@@ -179,12 +182,12 @@ def test_argument_errors_are_reported():
     torch.cuda.synchronize()
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("cfg", [LLAMA8B, RAGGED, LONG, FP8_70B],
                          ids=["llama3_8b_b64", "ragged_b128", "long_b16", "llama70b_fp8_b96"])
-def test_full_size_configs(oracle, cfg):
-    inp = synth.make_accept_inputs(cfg, seed=0)
-    compare(inp, oracle, label=cfg.name)
+def test_full_size_configs(oracle, cfg, seed):
+    inp = synth.make_accept_inputs(cfg, seed=seed)
+    compare(inp, oracle, label=f"{cfg.name} seed {seed}")
     if cfg is LLAMA8B:
-        compare(synth.make_accept_inputs(cfg, seed=0, greedy=True), oracle, label=cfg.name + " greedy")
-        for seed in (1, 2):
-            compare(synth.make_accept_inputs(cfg, seed=seed), oracle, label=f"{cfg.name} seed {seed}")
+        compare(synth.make_accept_inputs(cfg, seed=seed, greedy=True), oracle, label=f"{cfg.name} seed {seed} greedy")

@@ -93,3 +93,21 @@ def test_batches_larger_than_a_workgroup(oracle):
     binding.ss_kv_commit(d["q_indptr"], n, d["kv_len"])
     torch.cuda.synchronize()
     assert np.array_equal(d["kv_len"].cpu().numpy(), oracle.kv_commit(inp["q_indptr"], n.cpu().numpy(), inp["kv_len"]))
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (8, 4), (16, 4), (16, 2)], ids=["g1", "g2", "g4", "g8"])
+def test_tree_depth_20_tail_slots_stay_invisible(oracle, kv_dtype, hq, hkv):
+    # 21 new tokens whose first one sits at ctx % 16 == 12: the last tile's last lane group starts 32
+    # positions behind ctx, one past the mask word's last bit.  Those slots (and everything else past
+    # kv_len) hold NaN; a row that saw them would come out NaN or mis-normalised.
+    cfg = LLAMA8B.scaled(batch=6, num_q_heads=hq, num_kv_heads=hkv, kv_dtype=kv_dtype)
+    kv_len = np.array([33, 49, 705, 65, 45, 34], np.int32)     # the first four have (kv_len - 21) % 16 == 12
+    depth = np.array([20, 20, 20, 20, 20, 20], np.int32)
+    inp = synth.make_attention_inputs(cfg, seed=31, kv_len=kv_len, depth=depth, tree=True, nan_tail=True)
+    assert all((int(x) - 21) % 16 == 12 for x in kv_len[:4])
+    binding.ss_set_option("attn_path", 2)
+    try:
+        check(inp, oracle, max_q_len=21, label=f"tree depth 20, ctx%16==12, {kv_dtype} {hq}/{hkv}")
+    finally:
+        binding.ss_set_option("attn_path", 0)

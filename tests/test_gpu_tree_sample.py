@@ -26,28 +26,55 @@ def run_gpu(inp, max_q_len=0):
     return acc.cpu().numpy(), toks.cpu().numpy(), nodes.cpu().numpy(), ratio.cpu().numpy()
 
 
+def first_disagreement(k, gpu_nodes, gpu_ratio, ref_nodes, ref_ratio):
+    """Lowest-numbered node (1..k) whose treatment differs: offered by one side only, or accepted by one side only.
+
+    Nodes are offered in increasing node order (children follow their parent, later siblings follow a
+    rejected one), so the lowest differing node is the first decision the two walks do not share.
+    `*_ratio[i-1]` is NaN for a node that was never offered.  Returns 0 if every decision agrees."""
+    g_acc, r_acc = set(int(x) for x in gpu_nodes if x > 0), set(int(x) for x in ref_nodes if x > 0)
+    for i in range(1, k + 1):
+        g_off, r_off = not np.isnan(gpu_ratio[i - 1]), not np.isnan(ref_ratio[i - 1])
+        if g_off != r_off or ((i in g_acc) != (i in r_acc)):
+            return i
+    return 0
+
+
 def compare(inp, oracle, label, max_q_len=0):
     ref = oracle.tree_accept_sample(inp)
     acc, toks, nodes, ratio = run_gpu(inp, max_q_len)
-    excused = 0
+    excused, drafts = 0, 0
+    excused_req = set()
     for b in range(inp["batch"]):
+        d0, k = inp["q_indptr"][b] - b, int(inp["depth"][b])
+        drafts += k
         same = (acc[b] == ref["accepted_len"][b] and np.array_equal(toks[b], ref["out_tokens"][b])
                 and np.array_equal(nodes[b], ref["accepted_nodes"][b]))
         if same:
             continue
-        d0, k = inp["q_indptr"][b] - b, int(inp["depth"][b])
-        assert ref["near_tie"][d0:d0 + k].any(), (
-            f"{label}: request {b}: gpu n={acc[b]} tokens={toks[b].tolist()} nodes={nodes[b].tolist()} "
-            f"oracle n={ref['accepted_len'][b]} tokens={ref['out_tokens'][b].tolist()}")
+        # excused only if the first decision the two walks do not share is the accept/reject of a node that both
+        # offered and that the oracle flagged as a near-tie; a differing draw after identical decisions never is
+        i = first_disagreement(k, nodes[b], ratio[d0:d0 + k], ref["accepted_nodes"][b], ref["ratio"][d0:d0 + k])
+        ok = (i > 0 and not np.isnan(ratio[d0 + i - 1]) and not np.isnan(ref["ratio"][d0 + i - 1])
+              and ref["near_tie"][d0 + i - 1] == 1)
+        assert ok, (
+            f"{label}: request {b}: first differing node {i}: gpu n={acc[b]} tokens={toks[b].tolist()} nodes={nodes[b].tolist()} "
+            f"oracle n={ref['accepted_len'][b]} tokens={ref['out_tokens'][b].tolist()} nodes={ref['accepted_nodes'][b].tolist()}")
         excused += 1
+        excused_req.add(b)
+    # with p/q known to about 2e-6 relative, an excusal needs u within that of the ratio: a once-in-1e5 event per draft
+    assert excused <= max(1, int(1e-4 * drafts)), f"{label}: {excused} near-tie excusals among {drafts} drafts"
     Rd = inp["total_rows"] - inp["batch"]
     if Rd:
         r = ref["ratio"]
-        both = np.isfinite(r) & (r < 1e6) & np.isfinite(ratio[:Rd])
-        assert np.array_equal(np.isnan(r), np.isnan(ratio[:Rd])) or excused, f"{label}: different nodes were offered"
+        keep = np.ones(Rd, bool)
+        for b in excused_req:   # past an excused request's first difference the walks offer different nodes
+            keep[inp["q_indptr"][b] - b:inp["q_indptr"][b + 1] - b - 1] = False
+        assert np.array_equal(np.isnan(r[keep]), np.isnan(ratio[:Rd][keep])), f"{label}: different nodes were offered"
+        both = keep & np.isfinite(r) & (r < 1e6) & np.isfinite(ratio[:Rd])
         assert np.allclose(ratio[:Rd][both], r[both], rtol=2e-5, atol=1e-30), f"{label}: ratios differ"
-    print(f"[tree sample parity] {label}: {inp['batch']} requests, excused {excused}, mean accepted {acc.mean():.2f}, "
-          f"offered nodes {int(np.isfinite(ref['ratio']).sum())} of {Rd}")
+    print(f"[tree sample parity] {label}: {inp['batch']} requests, excused {excused}, flagged nodes {int(ref['near_tie'].sum())}, "
+          f"mean accepted {acc.mean():.2f}, offered nodes {int(np.isfinite(ref['ratio']).sum())} of {Rd}")
     return ref
 
 
@@ -72,9 +99,13 @@ def test_chain_parents_give_the_chain_result(oracle):
     inp["tree_parent"] = np.concatenate([np.arange(-1, k) for k in inp["depth"]]).astype(np.int32)
     acc, toks, nodes, _ = run_gpu(inp)
     chain = oracle.spec_accept(inp)
-    ok = [b for b in range(24) if acc[b] == chain["accepted_len"][b] and np.array_equal(toks[b], chain["out_tokens"][b])]
-    flagged = [b for b in range(24) if chain["near_tie"][inp["q_indptr"][b] - b:inp["q_indptr"][b + 1] - b - 1].any()]
-    assert set(range(24)) - set(ok) <= set(flagged)
+    for b in range(24):
+        if acc[b] == chain["accepted_len"][b] and np.array_equal(toks[b], chain["out_tokens"][b]):
+            continue
+        # only a different accepted length whose first differing draft the oracle flagged as a near-tie is excused
+        first, d0 = min(acc[b], chain["accepted_len"][b]), inp["q_indptr"][b] - b
+        assert (acc[b] != chain["accepted_len"][b] and first < inp["depth"][b] and chain["near_tie"][d0 + first] == 1
+                and np.array_equal(toks[b, :first], chain["out_tokens"][b, :first])), f"request {b}"
     compare(inp, oracle, "chain as tree")
 
 
