@@ -199,6 +199,29 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
                        void *stream);
 
 /*
+ * ss_spec_accept for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * ss_spec_accept minus the workspace: the partial results live in a static array of
+ * SS_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU the library is used on, held
+ * until the process ends).  The call allocates and frees nothing, on the device or the host, and
+ * never synchronises; option "validate" does not apply to it.
+ *   - A shape whose scratch need (ss_spec_accept_workspace) exceeds SS_STATIC_SCRATCH_BYTES is rejected with
+ *     SS_ERR_WORKSPACE before anything is launched (16 MiB serves e.g. 128 requests at depth 8 with a
+ *     152 064-entry vocabulary, or 200 requests at depth 20).
+ *   - All calls on one GPU share that GPU's array: calls that can overlap on one GPU (different streams,
+ *     different threads) race on it and must be serialised by the caller; calls on one stream are ordered.
+ *     The array keeps what the last call left; the kernels initialise whatever they read.
+ * ss_spec_accept_static_capacity returns SS_STATIC_SCRATCH_BYTES as the library was built.
+ */
+#define SS_STATIC_SCRATCH_BYTES (16u << 20)
+size_t ss_spec_accept_static_capacity(void);
+int32_t ss_spec_accept_static(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
+                              int32_t max_q_len, const int32_t *q_indptr, const void *target_logits,
+                              const void *draft_logits, const int32_t *draft_tokens, const float *u_accept,
+                              const float *u_sample, const float *temperature, float temperature_scalar, int32_t greedy,
+                              int32_t *accepted_len, int32_t *out_tokens, float *ratio_out, void *stream);
+
+/*
  * Greedy acceptance over draft trees (Section 2.2: dynamic draft trees, verified in one parallel
  * pass with the target's output preserved; here at temperature 0).  The new tokens of
  * request b form a tree: node 0 is the last accepted token, node i in 1..k carries draft token

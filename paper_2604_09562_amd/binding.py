@@ -22,7 +22,8 @@ SS_OUT_WIDTH = SS_MAX_DEPTH + 1
 _DT = {"f32": SS_F32, "bf16": SS_BF16, "fp8": SS_FP8_E4M3}
 
 EXPORTS = ("ss_version", "ss_last_error", "ss_spec_verify_attn_workspace", "ss_spec_verify_attn",
-           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_tree_greedy", "ss_spec_accept_tree_sample_workspace",
+           "ss_spec_accept_workspace", "ss_spec_accept", "ss_spec_accept_static", "ss_spec_accept_static_capacity",
+           "ss_spec_accept_tree_greedy", "ss_spec_accept_tree_sample_workspace",
            "ss_spec_accept_tree_sample", "ss_kv_append", "ss_kv_compact", "ss_kv_commit", "ss_depth_init",
            "ss_depth_update", "ss_route_select", "ss_set_option",
            "ss_profile_begin", "ss_profile_collect")
@@ -88,6 +89,14 @@ def lib() -> ctypes.CDLL:
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.ss_spec_accept_static.restype = ctypes.c_int32
+        L.ss_spec_accept_static.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p, ctypes.c_void_p]
+        L.ss_spec_accept_static_capacity.restype = ctypes.c_size_t
+        L.ss_spec_accept_static_capacity.argtypes = []
         L.ss_kv_append.restype = ctypes.c_int32
         L.ss_spec_accept_tree_greedy.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                                  ctypes.c_int32, ctypes.c_int32] + [ctypes.c_void_p] * 8 + [ctypes.c_size_t,
@@ -304,6 +313,24 @@ def ss_spec_accept(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens:
                                 _ptr(d["draft_tokens"]), _ptr(d["u_accept"]), _ptr(d["u_sample"]), _ptr(temp),
                                 ctypes.c_float(t_scalar), g, _ptr(accepted_len), _ptr(out_tokens), _ptr(ratio_out),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ss_spec_accept_static(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,
+                          ratio_out: Optional[torch.Tensor], *, greedy: Optional[bool] = None,
+                          per_request_temperature: bool = True, max_q_len: int = 0) -> None:
+    """ss_spec_accept without a workspace argument: the library's static device array holds the partial results."""
+    g = d["greedy"] if greedy is None else int(greedy)
+    temp = d["temperature"] if per_request_temperature else None
+    t_scalar = 0.0 if per_request_temperature else float(d["temperature_scalar"])
+    _check(lib().ss_spec_accept_static(d["batch"], d["vocab"], d["row_stride"], _DT[d["logit_dtype"]], d["total_rows"],
+                                       max_q_len, _ptr(d["q_indptr"]), _ptr(d["target_logits"]), _ptr(d["draft_logits"]),
+                                       _ptr(d["draft_tokens"]), _ptr(d["u_accept"]), _ptr(d["u_sample"]), _ptr(temp),
+                                       ctypes.c_float(t_scalar), g, _ptr(accepted_len), _ptr(out_tokens), _ptr(ratio_out),
+                                       _stream()))
+
+
+def ss_spec_accept_static_capacity() -> int:
+    return int(lib().ss_spec_accept_static_capacity())
 
 
 def ss_spec_accept_tree_greedy(d: Dict[str, object], accepted_len: torch.Tensor, out_tokens: torch.Tensor,

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecverify.so")
 # the per-grouping attention units take longest: start them first
-SOURCES = ["attn_mfma_g8.hip", "attn_mfma_g4.hip", "attn_mfma_g2.hip", "attn_mfma_g1.hip", "accept.hip", "accept_tree.hip", "api.hip",
+SOURCES = ["attn_mfma_g8.hip", "attn_mfma_g4.hip", "attn_mfma_g2.hip", "attn_mfma_g1.hip", "accept.hip", "accept_tree.hip", "accept_static.hip", "api.hip",
            "attn_mfma.hip", "attn_generic.hip", "kvcache.hip", "validate.hip", "depth_controller.cpp", "router.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -77,6 +77,57 @@ int attn_default_waves()
     return cus * 4;  // one wavefront per SIMD
 }
 
+// The checks and the launch behind ss_spec_accept; ss_spec_accept_static calls it with its own buffer and
+// without the optional metadata check (which synchronises and owns a pinned host record).
+int32_t spec_accept_call(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
+                         int32_t max_q_len, const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                         const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                         const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
+                         int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes, void *stream,
+                         bool apply_validate)
+{
+    if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
+    if (batch == 0) return SS_OK;
+    if (max_q_len < 0 || max_q_len > SS_OUT_WIDTH)
+        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
+    if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
+    if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
+        return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
+    const int64_t esz = logit_dtype == SS_F32 ? 4 : 2;
+    const int n_draft = total_rows - batch;
+    if (!q_indptr || !target_logits || !accepted_len || !out_tokens)
+        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (n_draft > 0 && (!draft_tokens || (!greedy && (!draft_logits || !u_accept))))
+        return fail(SS_ERR_INVALID_ARG, "draft-side arrays must be given when any request has drafts");
+    if (!greedy && !u_sample) return fail(SS_ERR_INVALID_ARG, "u_sample is required unless greedy");
+    if (!greedy && !temperature && !(temperature_scalar > 0.0f))
+        return fail(SS_ERR_INVALID_ARG, "temperature must be positive unless greedy");
+    if (!aligned16(target_logits) || (draft_logits && !aligned16(draft_logits)) || (row_stride * esz) % 16)
+        return fail(SS_ERR_INVALID_ARG, "logits rows must start 16-byte aligned (base and row_stride)");
+    const size_t need = accept_workspace_bytes(batch, total_rows, vocab);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
+    if (workspace_bytes < need)
+        return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (apply_validate && g_validate) {
+        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, max_q_len, static_cast<hipStream_t>(stream),
+                                    "ss_spec_accept");
+        if (rc == SS_OK)
+            rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
+                                 static_cast<hipStream_t>(stream), "ss_spec_accept");
+        if (rc != SS_OK) return rc;
+    }
+    AcceptArgs a{};
+    a.batch = batch; a.vocab = vocab; a.logit_dtype = logit_dtype; a.total_rows = total_rows; a.greedy = greedy ? 1 : 0;
+    a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft = draft_logits;
+    a.draft_tokens = draft_tokens; a.u_accept = u_accept; a.u_sample = u_sample; a.temperature = temperature;
+    a.temperature_scalar = temperature_scalar; a.accepted_len = accepted_len; a.out_tokens = out_tokens;
+    a.ratio_out = ratio_out; a.workspace = workspace;
+    a.max_q_len = max_q_len ? max_q_len : SS_OUT_WIDTH;
+    return accept_launch(a, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace ss
 
 using namespace ss;
@@ -310,46 +361,9 @@ int32_t ss_spec_accept(int32_t batch, int32_t vocab, int64_t row_stride, int32_t
                        const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
                        int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (batch < 0 || vocab <= 0 || total_rows < batch || (int64_t)total_rows > (int64_t)batch * SS_OUT_WIDTH)
-        return fail(SS_ERR_INVALID_ARG, "bad batch/total_rows/vocab (%d, %d, %d)", batch, total_rows, vocab);
-    if (batch == 0) return SS_OK;
-    if (max_q_len < 0 || max_q_len > SS_OUT_WIDTH)
-        return fail(SS_ERR_INVALID_ARG, "max_q_len must be 0 (unknown) or in [1, %d]", SS_OUT_WIDTH);
-    if (row_stride < vocab) return fail(SS_ERR_INVALID_ARG, "row_stride (%lld) < vocab (%d)", (long long)row_stride, vocab);
-    if (logit_dtype != SS_F32 && logit_dtype != SS_BF16)
-        return fail(SS_ERR_INVALID_ARG, "logit_dtype must be SS_F32 or SS_BF16");
-    const int64_t esz = logit_dtype == SS_F32 ? 4 : 2;
-    const int n_draft = total_rows - batch;
-    if (!q_indptr || !target_logits || !accepted_len || !out_tokens)
-        return fail(SS_ERR_INVALID_ARG, "a required device pointer is NULL");
-    if (n_draft > 0 && (!draft_tokens || (!greedy && (!draft_logits || !u_accept))))
-        return fail(SS_ERR_INVALID_ARG, "draft-side arrays must be given when any request has drafts");
-    if (!greedy && !u_sample) return fail(SS_ERR_INVALID_ARG, "u_sample is required unless greedy");
-    if (!greedy && !temperature && !(temperature_scalar > 0.0f))
-        return fail(SS_ERR_INVALID_ARG, "temperature must be positive unless greedy");
-    if (!aligned16(target_logits) || (draft_logits && !aligned16(draft_logits)) || (row_stride * esz) % 16)
-        return fail(SS_ERR_INVALID_ARG, "logits rows must start 16-byte aligned (base and row_stride)");
-    const size_t need = accept_workspace_bytes(batch, total_rows, vocab);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-        return fail(SS_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device buffer");
-    if (workspace_bytes < need)
-        return fail(SS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-    if (g_validate) {
-        int32_t rc = validate_batch(nullptr, nullptr, q_indptr, nullptr, batch, 0, 0, total_rows, max_q_len, static_cast<hipStream_t>(stream),
-                                    "ss_spec_accept");
-        if (rc == SS_OK)
-            rc = validate_accept(draft_tokens, u_accept, u_sample, temperature, batch, n_draft, vocab, greedy ? 1 : 0,
-                                 static_cast<hipStream_t>(stream), "ss_spec_accept");
-        if (rc != SS_OK) return rc;
-    }
-    AcceptArgs a{};
-    a.batch = batch; a.vocab = vocab; a.logit_dtype = logit_dtype; a.total_rows = total_rows; a.greedy = greedy ? 1 : 0;
-    a.row_stride = row_stride; a.q_indptr = q_indptr; a.target = target_logits; a.draft = draft_logits;
-    a.draft_tokens = draft_tokens; a.u_accept = u_accept; a.u_sample = u_sample; a.temperature = temperature;
-    a.temperature_scalar = temperature_scalar; a.accepted_len = accepted_len; a.out_tokens = out_tokens;
-    a.ratio_out = ratio_out; a.workspace = workspace;
-    a.max_q_len = max_q_len ? max_q_len : SS_OUT_WIDTH;
-    return accept_launch(a, static_cast<hipStream_t>(stream));
+    return spec_accept_call(batch, vocab, row_stride, logit_dtype, total_rows, max_q_len, q_indptr, target_logits,
+                            draft_logits, draft_tokens, u_accept, u_sample, temperature, temperature_scalar, greedy,
+                            accepted_len, out_tokens, ratio_out, workspace, workspace_bytes, stream, true);
 }
 
 // Host-visible checks shared by the calls that write the cache; *empty is set for a batch of zero requests.

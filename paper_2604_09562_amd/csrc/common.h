@@ -121,6 +121,12 @@ struct AcceptArgs {
 size_t accept_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_launch(const AcceptArgs &a, hipStream_t stream);
 int32_t accept_rowstats_launch(const AcceptArgs &a, hipStream_t stream);   // the first pass alone (row maxima and sums)
+int32_t spec_accept_call(int32_t batch, int32_t vocab, int64_t row_stride, int32_t logit_dtype, int32_t total_rows,
+                         int32_t max_q_len, const int32_t *q_indptr, const void *target_logits, const void *draft_logits,
+                         const int32_t *draft_tokens, const float *u_accept, const float *u_sample,
+                         const float *temperature, float temperature_scalar, int32_t greedy, int32_t *accepted_len,
+                         int32_t *out_tokens, float *ratio_out, void *workspace, size_t workspace_bytes, void *stream,
+                         bool apply_validate);   // argument checks + launch of ss_spec_accept
 size_t accept_tree_workspace_bytes(int batch, int total_rows, int vocab);
 int32_t accept_tree_sample_launch(const AcceptArgs &a, hipStream_t stream);
 
