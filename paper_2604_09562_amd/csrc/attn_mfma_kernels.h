@@ -46,6 +46,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
 constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
 constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
+constexpr int kPartRowStride = 33;   // float4 per staged partial row in LDS (32 of data + 1 of padding)
 
 // ---------------------------------------------------------------------------------------------
 // streaming kernel
@@ -75,6 +76,21 @@ __device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1)
     return r;
 }
 
+// KV tiles are read exactly once per call: non-temporal loads keep them from displacing what is reused
+// (partials, queries, the tile list) in the caches.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 stream_load16(const char *p)
+{
+    const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ uint2 stream_load8(const char *p)
+{
+    const u32x2 r = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+    return make_uint2(r.x, r.y);
+}
+
 template <bool FP8>
 struct TileRegs {
     // bf16: k[ks] = 8 bf16 of token (lane&15) at d = 32*ks + 8*(lane>>4)
@@ -99,13 +115,13 @@ __device__ __forceinline__ void load_tile(TileRegs<FP8> &t, const AttnArgs &a, c
     const char *kp = static_cast<const char *>(a.k) + blk + (lane & 15) * (D * ES) + (lane >> 4) * 16;
     const char *vp = static_cast<const char *>(a.v) + blk + (lane >> 4) * (4 * D * ES) + (lane & 15) * (8 * ES);
 #pragma unroll
-    for (int i = 0; i < (FP8 ? 2 : 4); ++i) t.k[i] = *reinterpret_cast<const uint4 *>(kp + i * 64);
+    for (int i = 0; i < (FP8 ? 2 : 4); ++i) t.k[i] = stream_load16(kp + i * 64);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if constexpr (FP8)
-            t.v[e] = *reinterpret_cast<const uint2 *>(vp + e * (D * ES));
+            t.v[e] = stream_load8(vp + e * (D * ES));
         else
-            t.v[e] = *reinterpret_cast<const uint4 *>(vp + e * (D * ES));
+            t.v[e] = stream_load16(vp + e * (D * ES));
     }
     if constexpr (FP8) {
         t.ks = k_scale[addr + vzero];
@@ -133,6 +149,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     // become scalar loads (own counter, no ordering against the vector KV loads).
     __shared__ int32_t id_lds[kWavesPerWg][kIdWindow];
     __shared__ uint4 q_lds[QLDS ? kWavesPerWg * NB * 4 * 64 : 1];
+    // one 16-row block of a partial per wave, rows 33 float4 apart (the odd stride spreads the rows over the banks)
+    __shared__ float4v o_lds[kWavesPerWg][16 * kPartRowStride];
     const int lane = threadIdx.x & 63;
     const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = blockIdx.x * kWavesPerWg + wslot;
@@ -240,6 +258,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
         float *po = a.part_o + slot * a.rows_pad * D;
         float *pml = a.part_ml + slot * a.rows_pad * 2;
+        // A lane holds 32 consecutive d of one row (d = 32*jq + 8*e + mb), in registers that are 16 bytes
+        // apart in memory: written directly, every store would scatter 16-byte pieces over 64 cache lines.
+        // The block goes through LDS instead and leaves as whole 512-byte rows, two per store.
+        float4v *ol = o_lds[wslot];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (nb < nbu) {
@@ -247,21 +269,26 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 l += __shfl_xor(l, 16);
                 l += __shfl_xor(l, 32);
                 const int n = nb * 16 + r16;
-                if (n < rows) {
-                    if (jq == 0) {
-                        pml[n * 2 + 0] = m_run[nb];
-                        pml[n * 2 + 1] = l;
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        // accumulator row 4*jq+e of M-block mb is d = 8*(4*jq+e) + mb
-                        float *dst = po + n * D + (jq * 4 + e) * 8;
-                        float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
-                        float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
-                        *reinterpret_cast<float4v *>(dst) = lo;
-                        *reinterpret_cast<float4v *>(dst + 4) = hi;
-                    }
+                if (n < rows && jq == 0) {
+                    pml[n * 2 + 0] = m_run[nb];
+                    pml[n * 2 + 1] = l;
                 }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // accumulator row 4*jq+e of M-block mb is d = 8*(4*jq+e) + mb
+                    const float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+                    const float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
+                    ol[r16 * kPartRowStride + jq * 8 + e * 2] = lo;
+                    ol[r16 * kPartRowStride + jq * 8 + e * 2 + 1] = hi;
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {   // same wave, LDS keeps program order: no barrier
+                    const int row = it * 2 + (lane >> 5), nn = nb * 16 + row;
+                    const float4v v = ol[row * kPartRowStride + (lane & 31)];
+                    if (nn < rows) *reinterpret_cast<float4v *>(po + nn * D + (lane & 31) * 4) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
             }
         }
         // next unit (its metadata is already in meta_*)
