@@ -47,6 +47,8 @@ constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax ref
 constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
 constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
 constexpr int kPartRowStride = 33;   // float4 per staged partial row in LDS (32 of data + 1 of padding)
+template <int NB>
+constexpr bool kChainMerge = NB <= 2;   // instances that combine the spans of a workgroup in LDS
 
 // ---------------------------------------------------------------------------------------------
 // streaming kernel
@@ -151,6 +153,17 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     __shared__ uint4 q_lds[QLDS ? kWavesPerWg * NB * 4 * 64 : 1];
     // one 16-row block of a partial per wave, rows 33 float4 apart (the odd stride spreads the rows over the banks)
     __shared__ float4v o_lds[kWavesPerWg][16 * kPartRowStride];
+    __shared__ float2 ml_lds[kWavesPerWg][16];
+    // CHAIN: the wavefronts of a workgroup own consecutive spans, so a unit that runs on from one span into the
+    // next is combined inside the workgroup: the right-hand wave leaves the result of its part in its deposit
+    // slot, the left-hand one folds it into its own.  Only what crosses a workgroup's edge goes to memory as a
+    // partial; a unit that lies inside one workgroup is finished here.
+    // (Only for one or two row blocks: with three the deposit slots take 100 KB and the ragged workload, the one
+    // that uses them, ran 7 % slower; beyond that the queries live in LDS and there is no room.)
+    constexpr bool CHAIN = kChainMerge<NB>;
+    __shared__ float4v dep_o[CHAIN ? kWavesPerWg : 1][CHAIN ? NB * 16 * kPartRowStride : 1];
+    __shared__ float2 dep_ml[CHAIN ? kWavesPerWg : 1][CHAIN ? NB * 16 : 1];
+    __shared__ int dep_flag[kWavesPerWg];   // 0 nothing yet; 1 deposited; 2 deposited and it reaches the unit's last tile
     const int lane = threadIdx.x & 63;
     const int wslot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wave = blockIdx.x * kWavesPerWg + wslot;
@@ -174,11 +187,14 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         for (int j = 0; j < kDescAddrs; ++j) desc_addr[j] = d[9 + j];
     }
     static_assert(NBUF - 1 <= kDescAddrs, "descriptor carries too few tile addresses");
+    if (lane == 0) dep_flag[wslot] = 0;
+    __syncthreads();   // the only barrier: every wave's flag is clear before any neighbour can look at it
     if (x0 >= x1) return;
 
     // ---- state of the unit being computed ----
     int span_left = (int)(x1 - x0);   // tiles of the span not yet computed
     int seg_left = 0;                 // of those, tiles that still belong to the current unit
+    int seg_tile0 = 0;                // the unit's tile the current segment began with
     int L = 0, q0 = 0, q_len = 0, rows = 0, nbu = 0;   // nbu: 16-row blocks the unit really has (for its partial)
     bf16x8 qreg[QLDS ? 1 : NB][4];    // Q as B operand: lane holds row 16*nb + r16, 8 consecutive d per k-step
     int lim[TREE ? 1 : NB];           // chain: last visible cache position of this lane's row in block nb
@@ -189,7 +205,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     const float sc2 = a.sm_scale * kLog2e;
 
     // (the metadata of the unit after the current one is fetched a unit ahead)
-    auto begin_unit_issue = [&]() {
+    auto begin_unit_issue = [&]() __attribute__((always_inline)) {
         L = meta_L;
         q0 = meta_q0;
         q_len = meta_q1 - meta_q0;
@@ -208,6 +224,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             }
         }
         seg_left = nb_tiles - tile < span_left ? nb_tiles - tile : span_left;
+        seg_tile0 = tile;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int n = nb * 16 + r16;
@@ -237,7 +254,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     };
     // Have the queries arrive here, inside the rarely taken branch, so that the steady-state path
     // never carries a pending load of them.
-    auto begin_unit_wait = [&]() {
+    auto begin_unit_wait = [&]() __attribute__((always_inline)) {
         if constexpr (!QLDS) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -250,28 +267,97 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         }
     };
 
-    auto end_unit = [&]() {
+    // A segment (the part of a unit that lies in this span) has ended: `starts` / `ends` say whether it holds
+    // the unit's first / last tile.
+    auto end_unit = [&](bool starts, bool ends) __attribute__((always_inline)) {
         // The accumulators were last written by MFMAs in another basic block: give them the wait
         // states a read needs before anything below touches them.
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-        const long long slot = (long long)wave + (long long)b * a.num_kv_heads + g;
+        float lsum[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float l = l_run[nb];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            lsum[nb] = l;
+        }
+        bool to_end = ends;   // does the result held here reach the unit's last tile?
+        if constexpr (CHAIN) {
+            if (!ends && wslot + 1 < kWavesPerWg) {
+                // The unit runs on into the right-hand neighbour's span, where it is that wave's first
+                // segment: finished long ago unless the spans are very short.  Fold its result into mine
+                // (mine first: a fixed order, so the bits do not depend on timing).
+                volatile int *fl = &dep_flag[wslot + 1];
+                int f = *fl;
+                while (f == 0) {
+                    __builtin_amdgcn_s_sleep(2);
+                    f = *fl;
+                }
+                to_end = f == 2;
+                const float4v *dq = dep_o[wslot + 1];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (nb < nbu) {
+                        const float2 ml2 = dep_ml[wslot + 1][nb * 16 + r16];
+                        const float m_new = fmaxf(m_run[nb], ml2.x);
+                        const float wa = exp2f(m_run[nb] - m_new), wb = exp2f(ml2.x - m_new);
+                        lsum[nb] = lsum[nb] * wa + ml2.y * wb;
+                        m_run[nb] = m_new;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float4v lo = dq[(nb * 16 + r16) * kPartRowStride + jq * 8 + e * 2];
+                            const float4v hi = dq[(nb * 16 + r16) * kPartRowStride + jq * 8 + e * 2 + 1];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                acc[c][nb][e] = acc[c][nb][e] * wa + lo[c] * wb;
+                                acc[4 + c][nb][e] = acc[4 + c][nb][e] * wa + hi[c] * wb;
+                            }
+                        }
+                    }
+                }
+            }
+            if (!starts && wslot > 0) {
+                // The unit began in the left-hand neighbour's span: leave the result for it.
+                float4v *dq = dep_o[wslot];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (nb < nbu) {
+                        if (jq == 0) dep_ml[wslot][nb * 16 + r16] = make_float2(m_run[nb], lsum[nb]);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+                            const float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
+                            dq[(nb * 16 + r16) * kPartRowStride + jq * 8 + e * 2] = lo;
+                            dq[(nb * 16 + r16) * kPartRowStride + jq * 8 + e * 2 + 1] = hi;
+                        }
+                    }
+                }
+                // the slot's contents are in LDS before the flag says so (LDS serves a wave's requests in order)
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                if (lane == 0) *(volatile int *)&dep_flag[wslot] = to_end ? 2 : 1;
+                return;
+            }
+        }
+        // What is held here goes to memory: as the finished output if it covers the whole unit, else as a
+        // partial in slot (workgroup, or wave without CHAIN) + unit, unique along the tile sequence.
+        const bool whole = CHAIN && starts && to_end;
+        const long long slot = (long long)(CHAIN ? (int)blockIdx.x : wave) + (long long)b * a.num_kv_heads + g;
         float *po = a.part_o + slot * a.rows_pad * D;
         float *pml = a.part_ml + slot * a.rows_pad * 2;
         // A lane holds 32 consecutive d of one row (d = 32*jq + 8*e + mb), in registers that are 16 bytes
         // apart in memory: written directly, every store would scatter 16-byte pieces over 64 cache lines.
-        // The block goes through LDS instead and leaves as whole 512-byte rows, two per store.
+        // The block goes through LDS instead and leaves as whole rows, two per store.
         float4v *ol = o_lds[wslot];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (nb < nbu) {
-                float l = l_run[nb];
-                l += __shfl_xor(l, 16);
-                l += __shfl_xor(l, 32);
                 const int n = nb * 16 + r16;
-                if (n < rows && jq == 0) {
+                if (whole) {
+                    if (jq == 0) ml_lds[wslot][r16] = make_float2(m_run[nb], lsum[nb]);
+                } else if (n < rows && jq == 0) {
                     pml[n * 2 + 0] = m_run[nb];
-                    pml[n * 2 + 1] = l;
+                    pml[n * 2 + 1] = lsum[nb];
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -286,12 +372,30 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 for (int it = 0; it < 8; ++it) {   // same wave, LDS keeps program order: no barrier
                     const int row = it * 2 + (lane >> 5), nn = nb * 16 + row;
                     const float4v v = ol[row * kPartRowStride + (lane & 31)];
-                    if (nn < rows) *reinterpret_cast<float4v *>(po + nn * D + (lane & 31) * 4) = v;
+                    if (whole) {
+                        // normalise, round to bf16 (nearest even), 256-byte output rows; lse from the row's (m, l)
+                        const float2 ml = ml_lds[wslot][row];
+                        const float inv = 1.f / ml.y;
+                        const int qi = a.q_lo + nn / G, hh = nn % G;
+                        const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
+                        const float2v lo2 = {v[0] * inv, v[1] * inv}, hi2 = {v[2] * inv, v[3] * inv};
+                        uint2 pk;
+                        pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo2, bf16x2));
+                        pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi2, bf16x2));
+                        if (nn < rows) {
+                            *reinterpret_cast<uint2 *>(static_cast<__bf16 *>(a.out) + orow * D + (lane & 31) * 4) = pk;
+                            if (a.lse && (lane & 31) == 0) a.lse[orow] = (ml.x + log2f(ml.y)) * kLn2;
+                        }
+                    } else if (nn < rows) {
+                        *reinterpret_cast<float4v *>(po + nn * D + (lane & 31) * 4) = v;
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
             }
         }
-        // next unit (its metadata is already in meta_*)
+    };
+    // (b, g) <- the unit after it (its metadata is already in meta_*)
+    auto next_unit = [&]() __attribute__((always_inline)) {
         tile = 0;
         if (++g == a.num_kv_heads) {
             g = 0;
@@ -307,7 +411,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     // The order of the pieces is chosen so that vector work that does not depend on a matrix result
     // follows each group of MFMAs: the V operands are built while S^T is in the matrix pipeline, and
     // a row block's exponentials while the previous block's output MFMAs run.
-    auto compute = [&](const TileRegs<FP8> &t, int ti) {
+    auto compute = [&](const TileRegs<FP8> &t, int ti) __attribute__((always_inline)) {
         const int tok0 = ti * kTile + jq * 4;   // first of this lane's four cache positions
 
         bf16x8 kop[4];
@@ -429,12 +533,13 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
 
     // one step of the compute side: consume a tile; at the end of a unit segment write its partial
     // and open the next segment (its query loads go out ahead of the next KV prefetch)
-    auto step = [&](const TileRegs<FP8> &t) {
+    auto step = [&](const TileRegs<FP8> &t) __attribute__((always_inline)) {
         compute(t, tile);
         ++tile;
         --span_left;
         if (--seg_left == 0) {
-            end_unit();
+            end_unit(seg_tile0 == 0, tile == nb_tiles);
+            next_unit();
             if (span_left > 0) {
                 begin_unit_issue();
                 begin_unit_wait();
@@ -468,7 +573,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
 
         int p_load = NBUF - 1;   // next tile of the window to load
         int id_v = ids[p_load < n ? p_load : n - 1];   // its address, read from LDS one step ahead of its use
-        auto issue = [&](TileRegs<FP8> &t) {
+        auto issue = [&](TileRegs<FP8> &t) __attribute__((always_inline)) {
             const int addr = __builtin_amdgcn_readfirstlane(id_v);
             ++p_load;
             id_v = ids[p_load < n ? p_load : n - 1];
@@ -521,8 +626,15 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     const long long off = (long long)pre * a.num_kv_heads + (long long)g * nb_tiles;
     // wave w covers tiles [w*total/nw, (w+1)*total/nw); the last wave starting at or before tile t
     // is ((t+1)*nw - 1) / total
-    const int w_first = (int)(((off + 1) * nw - 1) / total);
-    const int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
+    int w_first = (int)(((off + 1) * nw - 1) / total);
+    int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
+    if (a.chain) {
+        // the streaming kernel has combined the spans of each workgroup: one partial per workgroup the unit
+        // touches, and a unit inside a single workgroup is already finished
+        w_first /= kWavesPerWg;
+        w_last /= kWavesPerWg;
+        if (w_first == w_last) return;
+    }
 
     // running merge: (m, l, o) <- (m, l, o) (+) partial, both relative to their own reference m
     float m_all = kNoMax, l_all = 0.f;
@@ -557,7 +669,8 @@ int32_t launch_stream(const AttnArgs &a, hipStream_t stream, hipEvent_t ev0, hip
     // into a long tail.
     constexpr bool QLDS = NB >= 4;
     constexpr int NBUF = NB <= 3 ? 4 : (NB == 5 && !FP8) ? 2 : 3;
-    const AttnArgs &b = a;   // (the plan kernel has been enqueued by the caller)
+    AttnArgs b = a;   // (the plan kernel has been enqueued by the caller)
+    b.chain = kChainMerge<NB> ? 1 : 0;
     // When a profile is being taken the two events are attached to the dispatch itself, so that
     // their difference is the kernel's own duration on this stream (what a kernel trace shows).
     hipExtLaunchKernelGGL((attn_stream_kernel<G, NB, FP8, NBUF, QLDS, TREE>), dim3((unsigned)(b.launch_waves / kWavesPerWg)),

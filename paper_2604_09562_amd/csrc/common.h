@@ -86,6 +86,7 @@ struct AttnArgs {
     float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
     int32_t rows_pad;      // query rows per (request, kv head), padded to 16
     int32_t launch_waves;  // upper bound of streaming wavefronts (sizes the partial slots)
+    int32_t chain;         // set by the launcher: partials are per (workgroup, unit), units inside one workgroup are final
 };
 
 size_t attn_workspace_bytes(int batch, int max_blocks, int num_q_heads, int num_kv_heads, int head_dim,
