@@ -43,6 +43,15 @@ __device__ __forceinline__ void unpack(const uint4 &w, float (&x)[DT == SS_BF16 
     }
 }
 
+// Every logit is read exactly once by this pass: non-temporal loads keep the stream from displacing the one or
+// two rows per request that the later passes read again.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const char *p)
+{
+    const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a, Workspace w)
 {
@@ -73,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int i0 = base + v * (64 * vec) + lane * vec;
-            raw[v] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(row) + (int64_t)i0 * (DT == SS_BF16 ? 2 : 4));
+            raw[v] = stream_load16(static_cast<const char *>(row) + (int64_t)i0 * (DT == SS_BF16 ? 2 : 4));
         }
     } else {
         // the chunk that holds the end of the vocabulary: loads from a clamped, in-bounds address
