@@ -189,3 +189,36 @@ def test_commit_against_token_list_simulation(oracle):
         assert got[b] == len(kept)
     with pytest.raises(ValueError):
         oracle.kv_commit(np.array([0, 3], dtype=np.int32), np.array([3], dtype=np.int32), np.array([10], dtype=np.int32))
+
+
+def test_fp8_block_opened_by_a_small_token_clamps_later_ones(oracle):
+    # The storage rule fixes a block's scale from the values of the call that writes its slot 0 and never
+    # requantises.  A decode loop appends one token per step, so a block opened by a small-amplitude token
+    # sets the clamp for the fifteen that follow: this measures what that costs, so that the figure in the
+    # design notes has a test behind it.  Step 1 opens block 1 (position 16) with |x| <= 0.05, step 2 appends
+    # a token of N(0,1) values to position 17 of the same block.
+    D = 64
+    rng = np.random.default_rng(5)
+    small_tok = (0.05 * rng.uniform(-1, 1, D)).astype(np.float32)
+    big_tok = rng.standard_normal(D).astype(np.float32)
+    base = dict(batch=1, num_kv_heads=1, head_dim=D, block_size=16, max_blocks_per_seq=2, kv_dtype="fp8",
+                k_cache=np.zeros((2, 1, 16, D), dtype=np.uint8), v_cache=np.zeros((2, 1, 16, D), dtype=np.uint8),
+                k_scale=np.array([[0.01], [np.nan]], dtype=np.float32), v_scale=np.array([[0.01], [np.nan]], dtype=np.float32),
+                block_table=np.array([[0, 1]], dtype=np.int32), q_indptr=np.array([0, 1], dtype=np.int32), new_dtype="f32")
+    step1 = dict(base, kv_len=np.array([17], dtype=np.int32), k_new=small_tok.reshape(1, 1, D), v_new=small_tok.reshape(1, 1, D))
+    oracle.kv_append(step1)
+    scale = step1["k_scale"][1, 0]
+    assert scale == np.abs(small_tok).max() / np.float32(448.0)
+    step2 = dict(step1, kv_len=np.array([18], dtype=np.int32), k_new=big_tok.reshape(1, 1, D), v_new=big_tok.reshape(1, 1, D))
+    oracle.kv_append(step2)
+    assert step2["k_scale"][1, 0] == scale                                    # the block keeps its scale
+    stored = synth.decode_storage(step2["k_cache"][1, 0, 1], "fp8").astype(np.float64) * float(scale)
+    clamp = 448.0 * float(scale)                                              # = the opening token's amax
+    assert np.allclose(stored, np.clip(big_tok, -clamp, clamp), rtol=2 ** -4, atol=0)    # saturated at +-amax, else 3-bit rounding
+    saturated = np.abs(big_tok) > clamp
+    assert saturated.mean() > 0.9                                             # almost every value of the second token is clamped
+    # had the second token opened the block itself, its error would be the format's rounding only
+    fresh = dict(base, kv_len=np.array([17], dtype=np.int32), k_new=big_tok.reshape(1, 1, D), v_new=big_tok.reshape(1, 1, D))
+    oracle.kv_append(fresh)
+    own = synth.decode_storage(fresh["k_cache"][1, 0, 0], "fp8").astype(np.float64) * float(fresh["k_scale"][1, 0])
+    assert np.max(np.abs(own - big_tok) / np.maximum(np.abs(big_tok), 2.0 ** -6 * float(fresh["k_scale"][1, 0]) * 448)) <= 2 ** -4
