@@ -376,6 +376,8 @@ int32_t ss_route_select(const ss_worker_metrics *workers, int32_t n, const doubl
  * Options (process-wide, not thread-safe; meant for tests and measurement).
  *   "attn_path"     0 = automatic, 1 = force the plain fp32 vector kernel, 2 = require the MFMA kernel
  *   "attn_waves"    number of KV stream partitions (wavefronts) of the MFMA kernel, 0 = automatic
+ *   "attn_unit_weight"  what opening a (request, KV head) unit is taken to cost a wavefront, in KV tiles, when the
+ *                   KV stream is cut into partitions (default 3; 0 = partitions of equal tile counts)
  *   "validate"      1 = before launching, ss_spec_verify_attn, ss_kv_append and ss_spec_accept check the
  *                   device-resident metadata with a small kernel (row offsets, lengths against block counts,
  *                   block ids, draft tokens, temperatures, uniforms), synchronise the stream and return

@@ -29,6 +29,7 @@ int32_t hip_fail(hipError_t e, const char *what)
 static int64_t g_attn_path = 0;
 static int64_t g_attn_waves = 0;
 static int64_t g_validate = 0;
+static int64_t g_unit_weight = kUnitWeight;
 static std::vector<hipEvent_t> g_events;  // pairs
 static int g_prof_cap = 0, g_prof_used = 0;
 
@@ -152,6 +153,11 @@ int32_t ss_set_option(const char *name, int64_t value)
         g_attn_waves = value;
         return SS_OK;
     }
+    if (!strcmp(name, "attn_unit_weight")) {
+        if (value < 0 || value > 64) return fail(SS_ERR_INVALID_ARG, "attn_unit_weight must be in [0, 64]");
+        g_unit_weight = value;
+        return SS_OK;
+    }
     if (!strcmp(name, "validate")) {
         if (value < 0 || value > 1) return fail(SS_ERR_INVALID_ARG, "validate must be 0 or 1");
         g_validate = value;
@@ -213,6 +219,7 @@ int32_t ss_spec_verify_attn(const ss_paged_kv *kv, const ss_batch *batch, const 
     a.q_lo = 0;
     a.q_win = max_q_len;
     a.reuse_plan = (batch->flags & SS_BATCH_REUSE_PLAN) ? 1 : 0;
+    a.unit_weight = (int32_t)g_unit_weight;
     // carve the workspace
     char *w = static_cast<char *>(workspace);
     a.plan = reinterpret_cast<AttnPlan *>(w);

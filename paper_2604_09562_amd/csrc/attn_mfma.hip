@@ -26,33 +26,106 @@ namespace ss {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// plan: workgroup (b, g) sums the tile counts of the requests in front of b, writes the flat tile
-// address list of its unit, and (b, 0) / the last one publish the prefix and the partition count
+// plan: workgroup (b, g) writes the flat tile address list of its unit and the descriptors of the waves
+// whose span starts inside it; (b, 0) / the last one publish the prefix and the partition count.
+//
+// Where the spans are cut.  A wave pays a fixed price for every unit it opens (query loads, a drained
+// tile pipeline, the partial of the unit before: about the time of kUnitWeight tiles), so equal tile
+// counts do not finish together: on a ragged batch the waves that cross ten short units were 10 % late.
+// The cuts are therefore equal in a weighted coordinate in which every unit is kUnitWeight virtual
+// tiles followed by its real ones; a cut that falls into a unit's virtual part becomes the unit's first
+// tile.  The cuts depend on the batch's lengths only, so results do not vary from run to run.
 // ---------------------------------------------------------------------------------------------
+constexpr int kPlanMaxBatch = 4096;   // requests whose tile prefix fits the plan kernel's LDS; beyond that the cuts are unweighted
+
+struct WeightedSpace {
+    const int32_t *prefix;   // [batch+1] exclusive prefix of tiles per kv head
+    int batch, hkv, weight;
+    long long total_w;       // tiles of all units plus weight per unit
+    int nw;
+    __device__ long long wave_start(long long w) const { return w * total_w / nw; }   // weighted coordinate of wave w's cut
+    __device__ long long unit_start(int b, int g) const   // weighted coordinate of unit (b, g)
+    {
+        const int n = prefix[b + 1] - prefix[b];
+        return ((long long)prefix[b] + (long long)weight * b) * hkv + (long long)g * (n + weight);
+    }
+    // unit and tile that weighted coordinate y (< total_w) falls on, and the flat tile index
+    __device__ long long locate(long long y, int &b, int &g, int &tile) const
+    {
+        int lo = 0, hi = batch - 1;   // last request whose first unit starts at or before y
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (((long long)prefix[mid] + (long long)weight * mid) * hkv <= y) lo = mid; else hi = mid - 1;
+        }
+        b = lo;
+        const int n = prefix[b + 1] - prefix[b];
+        const long long r = y - ((long long)prefix[b] + (long long)weight * b) * hkv;
+        g = (int)(r / (n + weight));
+        const int in_unit = (int)(r - (long long)g * (n + weight)) - weight;
+        tile = in_unit > 0 ? in_unit : 0;
+        return (long long)prefix[b] * hkv + (long long)g * n + tile;
+    }
+};
+
 __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
 {
-    __shared__ int sh[8];
+    __shared__ int32_t prefix[kPlanMaxBatch + 1];
+    __shared__ int sh[4];
     const int b = blockIdx.x / a.num_kv_heads, g = blockIdx.x % a.num_kv_heads;
     const int tid = threadIdx.x;
-    int before = 0, rest = 0;   // tiles (per kv head) of the requests in front of b, and from b on
-    for (int i = tid; i < a.batch; i += 256) {
-        const int t = window_tiles(a.kv_len[i], a.q_indptr[i + 1] - a.q_indptr[i], a.q_lo);
-        if (i < b) before += t; else rest += t;
+    const bool weighted = a.batch <= kPlanMaxBatch && a.unit_weight > 0;
+
+    // exclusive prefix of the tile counts of all requests (every workgroup builds its own copy), or,
+    // for a batch too large for that, just the sums in front of and from request b on
+    int pre = 0;
+    long long total = 0;
+    if (a.batch <= kPlanMaxBatch) {
+        int carry = 0;
+        for (int base = 0; base < a.batch; base += 256) {
+            const int i = base + tid;
+            const int t = i < a.batch ? window_tiles(a.kv_len[i], a.q_indptr[i + 1] - a.q_indptr[i], a.q_lo) : 0;
+            int incl = t;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int o = __shfl_up(incl, off);
+                if ((tid & 63) >= off) incl += o;
+            }
+            if ((tid & 63) == 63) sh[tid >> 6] = incl;
+            __syncthreads();
+            int before = carry;
+            for (int wv = 0; wv < (tid >> 6); ++wv) before += sh[wv];
+            if (i < a.batch) prefix[i] = before + incl - t;
+            const int chunk_total = sh[0] + sh[1] + sh[2] + sh[3];
+            __syncthreads();
+            carry += chunk_total;
+        }
+        if (tid == 0) prefix[a.batch] = carry;
+        __syncthreads();
+        pre = prefix[b];
+        total = (long long)prefix[a.batch] * a.num_kv_heads;
+    } else {
+        int before = 0, rest = 0;
+        for (int i = tid; i < a.batch; i += 256) {
+            const int t = window_tiles(a.kv_len[i], a.q_indptr[i + 1] - a.q_indptr[i], a.q_lo);
+            if (i < b) before += t; else rest += t;
+        }
+        for (int off = 32; off; off >>= 1) {
+            before += __shfl_xor(before, off);
+            rest += __shfl_xor(rest, off);
+        }
+        __shared__ int sh2[8];
+        if ((tid & 63) == 0) {
+            sh2[tid >> 6] = before;
+            sh2[4 + (tid >> 6)] = rest;
+        }
+        __syncthreads();
+        pre = sh2[0] + sh2[1] + sh2[2] + sh2[3];
+        total = (long long)(pre + sh2[4] + sh2[5] + sh2[6] + sh2[7]) * a.num_kv_heads;
     }
-    for (int off = 32; off; off >>= 1) {
-        before += __shfl_xor(before, off);
-        rest += __shfl_xor(rest, off);
-    }
-    if ((tid & 63) == 0) {
-        sh[tid >> 6] = before;
-        sh[4 + (tid >> 6)] = rest;
-    }
-    __syncthreads();
-    const int pre = sh[0] + sh[1] + sh[2] + sh[3];
-    const long long total = (long long)(pre + sh[4] + sh[5] + sh[6] + sh[7]) * a.num_kv_heads;
     long long nw = total / kMinTilesPerWave;
     if (nw < 1) nw = 1;
     if (nw > a.launch_waves) nw = a.launch_waves;
+    const int weight = weighted ? a.unit_weight : 0;
+    const long long total_w = total + (long long)weight * a.batch * a.num_kv_heads;
 
     const int n = window_tiles(a.kv_len[b], a.q_indptr[b + 1] - a.q_indptr[b], a.q_lo);
     const long long off = (long long)pre * a.num_kv_heads + (long long)g * n;   // this unit's place in the flat list
@@ -60,20 +133,33 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     int32_t *dst = a.tile_addr + off;
     for (int t = tid; t < n; t += 256) dst[t] = bt[t] * a.num_kv_heads + g;
 
-    // waves whose span [w*total/nw, (w+1)*total/nw) starts inside this unit get their descriptor here
-    const long long w_lo = (off * nw + total - 1) / total;             // first w with w*total/nw >= off
-    const long long w_hi = ((off + n) * nw + total - 1) / total;       // first w with w*total/nw >= off + n
+    // waves whose cut falls into this unit's stretch [ya, ya + weight + n) of the weighted coordinate
+    const WeightedSpace ws{prefix, a.batch, a.num_kv_heads, weight, total_w, (int)nw};
+    const long long ya = off + (long long)weight * ((long long)b * a.num_kv_heads + g);
+    const long long w_lo = (ya * nw + total_w - 1) / total_w;                   // first w with w*total_w/nw >= ya
+    const long long w_hi = ((ya + weight + n) * nw + total_w - 1) / total_w;    // first w at or past the unit's end
     // Descriptor: {request, kv head, first tile, tiles of the unit, span begin, span end, kv_len,
     // first query row, end query row, addresses of the span's first kDescAddrs tiles}: everything
     // the wave's first loads depend on, so that they go out after a single read.
     for (long long w = w_lo + tid; w < w_hi && w < nw; w += 256) {
-        const long long x0 = w * total / nw, x1 = (w + 1) * total / nw;
+        const long long in_unit = w * total_w / nw - ya - weight;
+        const int t0 = in_unit > 0 ? (int)in_unit : 0;
+        const long long x0 = off + t0;
+        long long x1 = total;
+        if (w + 1 < nw) {
+            if (weight) {
+                int b1, g1, t1;
+                x1 = ws.locate((w + 1) * total_w / nw, b1, g1, t1);
+            } else {
+                x1 = (w + 1) * total / nw;
+            }
+        }
         int32_t *d = a.wave_desc + w * kDescInts;
-        d[0] = b; d[1] = g; d[2] = (int)(x0 - off); d[3] = n;
+        d[0] = b; d[1] = g; d[2] = t0; d[3] = n;
         d[4] = (int)x0; d[5] = (int)x1;
         d[6] = a.kv_len[b]; d[7] = a.q_indptr[b]; d[8] = a.q_indptr[b + 1];
         // walk forward from (b, g, tile) over unit boundaries; past the last unit repeat the last tile
-        int bb = b, gg = g, tt = (int)(x0 - off), nn = n, last = 0;
+        int bb = b, gg = g, tt = t0, nn = n, last = 0;
         const int32_t *tb = bt;
         for (int j = 0; j < kDescAddrs; ++j) {
             while (bb < a.batch && tt >= nn) {
@@ -104,6 +190,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
             a.tile_prefix[a.batch] = pre + n;
             a.plan->total_tiles = (int)total;
             a.plan->num_waves = (int)nw;
+            a.plan->unit_weight = weight;
         }
     }
 }

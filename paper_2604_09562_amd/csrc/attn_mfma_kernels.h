@@ -624,10 +624,15 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     const int pre = a.tile_prefix[b];
     const int nb_tiles = a.tile_prefix[b + 1] - pre;
     const long long off = (long long)pre * a.num_kv_heads + (long long)g * nb_tiles;
-    // wave w covers tiles [w*total/nw, (w+1)*total/nw); the last wave starting at or before tile t
-    // is ((t+1)*nw - 1) / total
-    int w_first = (int)(((off + 1) * nw - 1) / total);
-    int w_last = (int)(((off + nb_tiles) * nw - 1) / total);
+    // The spans were cut at w*total_w/nw in the weighted coordinate (every unit: `weight` virtual tiles, then
+    // its own); the last wave whose cut lies at or before coordinate t is ((t+1)*nw - 1) / total_w.  A cut
+    // inside the unit's virtual part starts at its first tile, so the unit's first wave is the last one at
+    // or before the end of that part, its last wave the last one before the next unit's stretch.
+    const long long weight = a.plan->unit_weight;
+    const long long total_w = total + weight * a.batch * a.num_kv_heads;
+    const long long ya = off + weight * unit;
+    int w_first = (int)(((ya + weight + 1) * nw - 1) / total_w);
+    int w_last = (int)(((ya + weight + nb_tiles) * nw - 1) / total_w);
     if (a.chain) {
         // the streaming kernel has combined the spans of each workgroup: one partial per workgroup the unit
         // touches, and a unit inside a single workgroup is already finished

@@ -29,6 +29,7 @@ constexpr int kDescInts = 16;            // ints per wave descriptor
 constexpr int kDescAddrs = 4;            // tile addresses a descriptor carries for the span's first tiles
 constexpr int kMfmaHeadDim = 128;        // head_dim the matrix-core kernel is written for
 constexpr int kMaxRowBlocks = 5;         // 16-row blocks of query rows one wavefront can keep accumulators for
+constexpr int kUnitWeight = 3;           // default cost of opening a unit, in tiles, for the span cuts
 
 // Query tokens of a request that fall into the pass's window, and the KV tiles its units stream in this
 // pass: a request without rows in the window keeps one tile so that no unit of the flat tile space is empty.
@@ -54,7 +55,8 @@ __host__ __device__ inline int window_tiles(int kv_len, int q_len, int q_lo)
 struct AttnPlan {
     int32_t total_tiles;   // sum over requests of ceil(kv_len/16) * num_kv_heads
     int32_t num_waves;     // partitions actually used (<= launched wavefronts)
-    int32_t pad[2];
+    int32_t unit_weight;   // virtual tiles per unit in the coordinate the spans were cut in (0: plain tile counts)
+    int32_t pad;
 };
 
 struct AttnArgs {
@@ -86,6 +88,7 @@ struct AttnArgs {
     float *part_ml;        // [slots][rows_pad][2]  (log2-domain max, sum)
     int32_t rows_pad;      // query rows per (request, kv head), padded to 16
     int32_t launch_waves;  // upper bound of streaming wavefronts (sizes the partial slots)
+    int32_t unit_weight;   // what opening a unit costs a wave, in tiles (weights the span cuts; 0 = equal tile counts)
     int32_t chain;         // set by the launcher: partials are per (workgroup, unit), units inside one workgroup are final
 };
 
