@@ -288,11 +288,11 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 // The unit runs on into the right-hand neighbour's span, where it is that wave's first
                 // segment: finished long ago unless the spans are very short.  Fold its result into mine
                 // (mine first: a fixed order, so the bits do not depend on timing).
-                volatile int *fl = &dep_flag[wslot + 1];
-                int f = *fl;
+                // (relaxed LDS accesses: a volatile or acquiring load would first wait for every tile in flight)
+                int f = __hip_atomic_load(&dep_flag[wslot + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 while (f == 0) {
                     __builtin_amdgcn_s_sleep(2);
-                    f = *fl;
+                    f = __hip_atomic_load(&dep_flag[wslot + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
                 to_end = f == 2;
                 const float4v *dq = dep_o[wslot + 1];
@@ -333,9 +333,11 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                         }
                     }
                 }
-                // the slot's contents are in LDS before the flag says so (LDS serves a wave's requests in order)
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                if (lane == 0) *(volatile int *)&dep_flag[wslot] = to_end ? 2 : 1;
+                // The slot's contents are in LDS before the flag says so: LDS serves a wave's requests in order,
+                // and the wait below covers LDS only (a release fence would also wait for the tiles in flight).
+                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+                __builtin_amdgcn_wave_barrier();
+                if (lane == 0) __hip_atomic_store(&dep_flag[wslot], to_end ? 2 : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 return;
             }
         }
@@ -368,13 +370,23 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                     ol[r16 * kPartRowStride + jq * 8 + e * 2 + 1] = hi;
                 }
                 __builtin_amdgcn_wave_barrier();
+                // same wave, LDS keeps program order: no barrier.  All rows are read back first, in straight-line
+                // code, so that the LDS latency is paid once and not in front of every store.
+                float4v rowv[8];
+                float2 rowml[8];
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {   // same wave, LDS keeps program order: no barrier
+                for (int it = 0; it < 8; ++it) {
+                    const int row = it * 2 + (lane >> 5);
+                    rowv[it] = ol[row * kPartRowStride + (lane & 31)];
+                    if (whole) rowml[it] = ml_lds[wslot][row];
+                }
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
                     const int row = it * 2 + (lane >> 5), nn = nb * 16 + row;
-                    const float4v v = ol[row * kPartRowStride + (lane & 31)];
+                    const float4v v = rowv[it];
                     if (whole) {
                         // normalise, round to bf16 (nearest even), 256-byte output rows; lse from the row's (m, l)
-                        const float2 ml = ml_lds[wslot][row];
+                        const float2 ml = rowml[it];
                         const float inv = 1.f / ml.y;
                         const int qi = a.q_lo + nn / G, hh = nn % G;
                         const long long orow = (long long)(q0 + qi) * a.num_q_heads + g * G + hh;
