@@ -1,12 +1,17 @@
 """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU).
 
 Every source is compiled to an object of its own, several at a time, then linked; the objects live
-in ``_build/`` next to this file.
+in ``_build/`` next to this file.  The compiler's per-kernel resource remarks are collected into
+``_build/resources.txt`` (registers, scratch bytes per lane, LDS per kernel): the place to look when a change
+to the streaming attention kernel makes an instance an order of magnitude slower, which is what happens when
+its tile ring or accumulators no longer fit the register file.  (The instances with four and five row blocks
+spill some values at entry that only the end of a unit reloads; their tile bodies touch no scratch.)
 """
 from __future__ import annotations
 
 import concurrent.futures
 import os
+import re
 import subprocess
 import sys
 
@@ -20,7 +25,8 @@ SOURCES = ["attn_mfma_g8.hip", "attn_mfma_g4.hip", "attn_mfma_g2.hip", "attn_mfm
            "attn_mfma.hip", "attn_generic.hip", "kvcache.hip", "validate.hip", "depth_controller.cpp", "router.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # the host pass reports that it does not know the packed-fp32 feature; that line is noise
 NOISE = "is not a recognized feature for this target"
 
@@ -29,10 +35,25 @@ def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in res.stderr.splitlines() if NOISE not in l)
+    lines = [l for l in res.stderr.splitlines() if NOISE not in l]
+    err = "\n".join(l for l in lines if "remark:" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + err)
-    return err
+    return err, _resources(lines)
+
+
+def _resources(lines):
+    """{mangled kernel name: {"VGPRs": n, "AGPRs": n, "ScratchSize": bytes per lane, "LDS Size": bytes}} from the remarks."""
+    out, cur = {}, None
+    for l in lines:
+        m = re.search(r"remark: .*Function Name: (\S+)", l)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark: .*?\s(VGPRs|AGPRs|ScratchSize|LDS Size)[^:]*: (\d+)", l)
+        if m and cur is not None:
+            cur.setdefault(m.group(1), int(m.group(2)))
+    return out
 
 
 def build(verbose: bool = False, jobs: int = 0) -> str:
@@ -42,8 +63,15 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
         futs = [pool.submit(_run, ["hipcc", *FLAGS, "-c", os.path.join(CSRC, s), "-o", o], verbose)
                 for s, o in zip(SOURCES, objects)]
-        warnings = [f.result() for f in futs]   # raises the first failure
-    warnings.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objects], verbose))
+        results = [f.result() for f in futs]   # raises the first failure
+    warnings = [r[0] for r in results]
+    report = {}
+    for r in results:
+        report.update(r[1])
+    with open(os.path.join(OBJ, "resources.txt"), "w") as f:
+        for name in sorted(report):
+            f.write(name + " " + " ".join(f"{k.replace(' ', '_')}={v}" for k, v in report[name].items()) + "\n")
+    warnings.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objects], verbose)[0])
     if verbose:
         for w in warnings:
             if w.strip():

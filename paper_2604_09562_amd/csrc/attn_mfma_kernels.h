@@ -5,13 +5,19 @@
 // Work decomposition.  The KV cache of one (request, KV head) pair ("unit") is a run of
 // 16-token tiles, one per cache block.  All tiles of all units form one flat sequence (unit
 // major).  A plan kernel writes that sequence out as a flat list of tile addresses (physical
-// block * kv heads + kv head) and cuts it into `num_waves` equal contiguous spans; every
-// wavefront streams one span, so the load is balanced whatever the mix of context lengths, and
-// the load side of the kernel is a plain linear walk that never stops at a unit boundary.  A
-// span may cover the tail of one unit, several whole units and the head of another; for every
-// unit it touches the wave emits one partial result (softmax reference, sum, unnormalised
-// output) into slot `wave + unit` (that sum is unique along the sequence).  A last kernel
-// merges the partials of each unit by their log-sum-exp and writes the rounded output.
+// block * kv heads + kv head) and cuts it into `num_waves` contiguous spans of equal cost (a
+// tile costs one, opening a unit costs a fixed number of tiles); every wavefront streams one
+// span, so the load is balanced whatever the mix of context lengths, and the load side of the
+// kernel is a plain linear walk that never stops at a unit boundary.  A span may cover the tail
+// of one unit, several whole units and the head of another; for every unit it touches the wave
+// has one partial result (softmax reference, sum, unnormalised output).  In the instances with
+// at most two row blocks the four wavefronts of a workgroup, whose spans are consecutive, hand
+// the partials of a shared unit from right to left through LDS and combine them by their
+// log-sum-exp; a unit that lies inside one workgroup's spans is normalised, rounded and
+// written by that workgroup.  What is left (a unit that crosses workgroups; every split unit
+// in the other instances) goes to device memory as a partial in slot `workgroup + unit`
+// (`wave + unit` without the LDS hand-over; unique along the sequence either way), and a last
+// kernel merges those partials in span order and writes the rounded output.
 //
 // Per tile, with rows = (k+1) * (query heads per KV head) padded to a multiple of 16:
 //   S^T[token][row] = K[token][:] . Q[row][:]   v_mfma_f32_16x16x32_bf16, K tile as A operand
@@ -92,6 +98,14 @@ __device__ __forceinline__ uint2 stream_load8(const char *p)
     const u32x2 r = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
     return make_uint2(r.x, r.y);
 }
+
+// Output accumulators live in the accumulator registers (the matrix instructions are selected in that form
+// once a kernel needs more than 256 registers).  A value that ordinary vector arithmetic produced -- the zero
+// of a new unit, a rescaled or merged accumulator -- is handed over through this empty statement, so that
+// every value flowing into the tile loop comes from an accumulator register; otherwise the compiler keeps the
+// loop-carried accumulators in vector registers and moves all of them to the accumulator file and back on
+// every tile.
+__device__ __forceinline__ void to_accumulator_file(float4v &c) { asm volatile("" : "+a"(c)); }
 
 template <bool FP8>
 struct TileRegs {
@@ -249,7 +263,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             m_run[nb] = kNoMax;
             l_run[nb] = 0.f;
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb) acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int mb = 0; mb < 8; ++mb) {
+                acc[mb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+                to_accumulator_file(acc[mb][nb]);
+            }
         }
     };
     // Have the queries arrive here, inside the rarely taken branch, so that the steady-state path
@@ -522,24 +539,69 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
                 l_run[nb] *= alpha;
 #pragma unroll
-                for (int mb = 0; mb < 8; ++mb) acc[mb][nb] *= alpha;
+                for (int mb = 0; mb < 8; ++mb) {
+                    acc[mb][nb] *= alpha;
+                    to_accumulator_file(acc[mb][nb]);
+                }
                 m_run[nb] = m_new;
             }
         }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
-            l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-            const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+        if constexpr (NB >= 3) {
+            // A wavefront issues in order: matrix instructions that stand back to back leave the vector ALU idle
+            // while they run, and the vector work of a row block leaves the matrix pipeline idle.  With many row
+            // blocks the kernel is bound by that, not by memory, so the blocks are software-pipelined by hand: the
+            // exponentials and the packing of block nb+1 are cut into pieces of two or three instructions, one after
+            // each of block nb's eight output MFMAs, and a scheduling barrier after every piece keeps the compiler
+            // from gathering the matrix instructions together again.
+            float pd[4], pe[4];
             uint2 pk;
-            pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-            pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-            const short4v pop = __builtin_bit_cast(short4v, pk);
+            auto piece = [&](int nb, int i) __attribute__((always_inline)) {
+                if (i == 0) { pd[0] = sv[nb][0] - m_run[nb]; pd[1] = sv[nb][1] - m_run[nb]; }
+                if (i == 1) { pd[2] = sv[nb][2] - m_run[nb]; pd[3] = sv[nb][3] - m_run[nb]; }
+                if (i == 2) { pe[0] = __builtin_amdgcn_exp2f(pd[0]); pe[1] = __builtin_amdgcn_exp2f(pd[1]); }
+                if (i == 3) { pe[2] = __builtin_amdgcn_exp2f(pd[2]); pe[3] = __builtin_amdgcn_exp2f(pd[3]); }
+                if (i == 4) l_run[nb] += (pe[0] + pe[1]) + (pe[2] + pe[3]);
+                if (i == 5) {
+                    const float2v lo = {pe[0] * t.vs, pe[1] * t.vs};
+                    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+                }
+                if (i == 6) {
+                    const float2v hi = {pe[2] * t.vs, pe[3] * t.vs};
+                    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+                }
+            };
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
+            for (int i = 0; i < 7; ++i) piece(0, i);
+            short4v pop = __builtin_bit_cast(short4v, pk);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) {
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
+                    if (nb + 1 < NB) {
+                        piece(nb + 1, mb);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (nb + 1 < NB) pop = __builtin_bit_cast(short4v, pk);
+            }
+        } else {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                float p[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
+                l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+                const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
+                uint2 pk;
+                pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+                pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+                const short4v pop = __builtin_bit_cast(short4v, pk);
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vop[mb], pop, acc[mb][nb], 0, 0, 0);
+            }
         }
     };
 
