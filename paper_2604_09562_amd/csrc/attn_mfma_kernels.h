@@ -55,6 +55,9 @@ constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a
 constexpr int kPartRowStride = 33;   // float4 per staged partial row in LDS (32 of data + 1 of padding)
 template <int NB>
 constexpr bool kChainMerge = NB <= 2;   // instances that combine the spans of a workgroup in LDS
+template <int NB>
+constexpr bool kStageRows = NB <= 4;    // instances that write partials as whole rows through LDS (measured: with five
+                                        // row blocks the staging costs more than the scattered stores it replaces)
 
 // ---------------------------------------------------------------------------------------------
 // streaming kernel
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     __shared__ int32_t id_lds[kWavesPerWg][kIdWindow];
     __shared__ uint4 q_lds[QLDS ? kWavesPerWg * NB * 4 * 64 : 1];
     // one 16-row block of a partial per wave, rows 33 float4 apart (the odd stride spreads the rows over the banks)
-    __shared__ float4v o_lds[kWavesPerWg][16 * kPartRowStride];
+    __shared__ float4v o_lds[kStageRows<NB> ? kWavesPerWg : 1][kStageRows<NB> ? 16 * kPartRowStride : 1];
     __shared__ float2 ml_lds[kWavesPerWg][16];
     // CHAIN: the wavefronts of a workgroup own consecutive spans, so a unit that runs on from one span into the
     // next is combined inside the workgroup: the right-hand wave leaves the result of its part in its deposit
@@ -366,8 +369,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         float *pml = a.part_ml + slot * a.rows_pad * 2;
         // A lane holds 32 consecutive d of one row (d = 32*jq + 8*e + mb), in registers that are 16 bytes
         // apart in memory: written directly, every store would scatter 16-byte pieces over 64 cache lines.
-        // The block goes through LDS instead and leaves as whole rows, two per store.
-        float4v *ol = o_lds[wslot];
+        // The block goes through LDS instead and leaves as whole rows, two per store (kStageRows).
+        float4v *ol = o_lds[kStageRows<NB> ? wslot : 0];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (nb < nbu) {
@@ -377,6 +380,19 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 } else if (n < rows && jq == 0) {
                     pml[n * 2 + 0] = m_run[nb];
                     pml[n * 2 + 1] = lsum[nb];
+                }
+                if constexpr (!kStageRows<NB>) {
+                    if (n < rows) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {   // accumulator row 4*jq+e of M-block mb is d = 8*(4*jq+e) + mb
+                            float *dst = po + n * D + (jq * 4 + e) * 8;
+                            const float4v lo = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+                            const float4v hi = {acc[4][nb][e], acc[5][nb][e], acc[6][nb][e], acc[7][nb][e]};
+                            *reinterpret_cast<float4v *>(dst) = lo;
+                            *reinterpret_cast<float4v *>(dst + 4) = hi;
+                        }
+                    }
+                    continue;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
