@@ -109,6 +109,17 @@ __device__ __forceinline__ uint2 stream_load8(const char *p)
 // loop-carried accumulators in vector registers and moves all of them to the accumulator file and back on
 // every tile.
 __device__ __forceinline__ void to_accumulator_file(float4v &c) { asm volatile("" : "+a"(c)); }
+// The opposite direction for the rare rescale: the move is written out, so that it stays inside the rarely taken
+// branch (left to the compiler, the moves of all accumulators to vector registers can end up in front of the
+// branch, on every tile).  The compiler does not look into the statement: the caller leaves the wait states
+// between the last matrix instruction that wrote the register and this read (accumulator_read_guard).
+__device__ __forceinline__ float from_accumulator_file(float x)
+{
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(x));
+    return r;
+}
+__device__ __forceinline__ void accumulator_read_guard() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
 
 template <bool FP8>
 struct TileRegs {
@@ -531,21 +542,33 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         float sv[NB][4];
         bool trig = false;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if constexpr (TREE) {
-                // Positions past the cache end are past the mask's last set bit.
-                const uint32_t vis = tree_visible4(newmask[nb], tok0 - ctx);
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? s[nb][e] * kscale : -INFINITY;
-            } else {
+            for (int e = 0; e < 4; ++e) sv[nb][e] = s[nb][e] * kscale;
+        // Every row sees all of the context before the request's new tokens, so only the last tile or two of a
+        // unit need the selects: the wave-uniform test skips them for the rest.
+        if (ti * kTile + kTile > ctx) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                    sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : s[nb][e] * kscale;
+            for (int nb = 0; nb < NB; ++nb) {
+                if constexpr (TREE) {
+                    // Positions past the cache end are past the mask's last set bit.
+                    const uint32_t vis = tree_visible4(newmask[nb], tok0 - ctx);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? sv[nb][e] : -INFINITY;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
+                        sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : sv[nb][e];
+                }
             }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
             const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
             trig |= lane_mx > m_run[nb] + kSlack;
         }
         if (__any(trig)) {
+            accumulator_read_guard();
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
@@ -556,8 +579,11 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 l_run[nb] *= alpha;
 #pragma unroll
                 for (int mb = 0; mb < 8; ++mb) {
-                    acc[mb][nb] *= alpha;
-                    to_accumulator_file(acc[mb][nb]);
+                    const float4v c = acc[mb][nb];
+                    float4v r = {from_accumulator_file(c[0]) * alpha, from_accumulator_file(c[1]) * alpha,
+                                 from_accumulator_file(c[2]) * alpha, from_accumulator_file(c[3]) * alpha};
+                    to_accumulator_file(r);
+                    acc[mb][nb] = r;
                 }
                 m_run[nb] = m_new;
             }
