@@ -507,10 +507,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                     s[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[ks], qreg[nb][ks], s[nb], 0, 0, 0);
         }
 
-        // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.  Slots at or past
-        // kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot occur.
-        const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
-        const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
+        // V operand registers: vop[mb] = d-phase mb of tokens tok0 .. tok0+3.
         short4v vop[8];
 #pragma unroll
         for (int h = 0; h < 4; ++h) {   // word h of each token's 8 values holds d-phases 2h and 2h+1
@@ -527,51 +524,72 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 }
             }
             uint2 lo, hi;
-            lo.x = pack_lo16(w[0], w[1]) & m01;
-            lo.y = pack_lo16(w[2], w[3]) & m23;
-            hi.x = pack_hi16(w[0], w[1]) & m01;
-            hi.y = pack_hi16(w[2], w[3]) & m23;
+            lo.x = pack_lo16(w[0], w[1]);
+            lo.y = pack_lo16(w[2], w[3]);
+            hi.x = pack_hi16(w[0], w[1]);
+            hi.y = pack_hi16(w[2], w[3]);
             vop[2 * h] = __builtin_bit_cast(short4v, lo);
             vop[2 * h + 1] = __builtin_bit_cast(short4v, hi);
+        }
+        // Slots at or past kv_len may hold anything (NaN, inf): they are cleared so that 0 * garbage cannot
+        // occur.  Only the last tile of a cache has such slots; the e4m3 instances, which are bound by their
+        // vector instructions, test for it (wave-uniform), the others clear unconditionally (measured: there the
+        // branch costs more than the sixteen ANDs).
+        if (!FP8 || ti * kTile + kTile > L) {
+            const uint32_t m01 = (tok0 + 0 < L ? 0x0000ffffu : 0u) | (tok0 + 1 < L ? 0xffff0000u : 0u);
+            const uint32_t m23 = (tok0 + 2 < L ? 0x0000ffffu : 0u) | (tok0 + 3 < L ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) {
+                uint2 w = __builtin_bit_cast(uint2, vop[mb]);
+                w.x &= m01;
+                w.y &= m23;
+                vop[mb] = __builtin_bit_cast(short4v, w);
+            }
         }
 
         // Online softmax with a lagging reference: p = 2^(s - m_ref).  The reference only moves
         // (and the accumulators are rescaled) when some score exceeds it by more than kSlack, so
-        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.
+        // p <= 2^kSlack and the common tile needs no cross-lane traffic and no rescale.  The common path forms
+        // the exponent's argument with one fused multiply-add per score and tests all of them against the slack
+        // at once; the scores themselves are only formed on the rare path (before a unit's first tile the
+        // reference is so low that the argument has absorbed them).
         const float kscale = sc2 * t.ks;
-        float sv[NB][4];
-        bool trig = false;
+        float pd[NB][4];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sv[nb][e] = s[nb][e] * kscale;
+            for (int e = 0; e < 4; ++e) pd[nb][e] = __builtin_fmaf(s[nb][e], kscale, -m_run[nb]);
         // Every row sees all of the context before the request's new tokens, so only the last tile or two of a
         // unit need the selects: the wave-uniform test skips them for the rest.
-        if (ti * kTile + kTile > ctx) {
+        const bool tail = ti * kTile + kTile > ctx;
+        if (tail) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 if constexpr (TREE) {
                     // Positions past the cache end are past the mask's last set bit.
                     const uint32_t vis = tree_visible4(newmask[nb], tok0 - ctx);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) sv[nb][e] = ((vis >> e) & 1u) ? sv[nb][e] : -INFINITY;
+                    for (int e = 0; e < 4; ++e) pd[nb][e] = ((vis >> e) & 1u) ? pd[nb][e] : -INFINITY;
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)   // causal limit among the new tokens / end of the cache
-                        sv[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : sv[nb][e];
+                        pd[nb][e] = (tok0 + e > lim[nb]) ? -INFINITY : pd[nb][e];
                 }
             }
         }
+        float top = pd[0][0];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const float lane_mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
-            trig |= lane_mx > m_run[nb] + kSlack;
-        }
-        if (__any(trig)) {
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) top = fmaxf(top, pd[nb][e]);
+        if (__any(top > kSlack)) {
             accumulator_read_guard();
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                float mx = fmaxf(fmaxf(sv[nb][0], sv[nb][1]), fmaxf(sv[nb][2], sv[nb][3]));
+                float sv[4];   // the scores, masked where the argument was
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sv[e] = pd[nb][e] == -INFINITY ? -INFINITY : s[nb][e] * kscale;
+                float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float m_new = fmaxf(m_run[nb], mx);
@@ -586,6 +604,8 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                     acc[mb][nb] = r;
                 }
                 m_run[nb] = m_new;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pd[nb][e] = sv[e] - m_new;
             }
         }
         if constexpr (NB >= 3) {
@@ -595,13 +615,13 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             // exponentials and the packing of block nb+1 are cut into pieces of two or three instructions, one after
             // each of block nb's eight output MFMAs, and a scheduling barrier after every piece keeps the compiler
             // from gathering the matrix instructions together again.
-            float pd[4], pe[4];
+            float pe[4];
             uint2 pk;
             auto piece = [&](int nb, int i) __attribute__((always_inline)) {
-                if (i == 0) { pd[0] = sv[nb][0] - m_run[nb]; pd[1] = sv[nb][1] - m_run[nb]; }
-                if (i == 1) { pd[2] = sv[nb][2] - m_run[nb]; pd[3] = sv[nb][3] - m_run[nb]; }
-                if (i == 2) { pe[0] = __builtin_amdgcn_exp2f(pd[0]); pe[1] = __builtin_amdgcn_exp2f(pd[1]); }
-                if (i == 3) { pe[2] = __builtin_amdgcn_exp2f(pd[2]); pe[3] = __builtin_amdgcn_exp2f(pd[3]); }
+                if (i == 0) pe[0] = __builtin_amdgcn_exp2f(pd[nb][0]);
+                if (i == 1) pe[1] = __builtin_amdgcn_exp2f(pd[nb][1]);
+                if (i == 2) pe[2] = __builtin_amdgcn_exp2f(pd[nb][2]);
+                if (i == 3) pe[3] = __builtin_amdgcn_exp2f(pd[nb][3]);
                 if (i == 4) l_run[nb] += (pe[0] + pe[1]) + (pe[2] + pe[3]);
                 if (i == 5) {
                     const float2v lo = {pe[0] * t.vs, pe[1] * t.vs};
@@ -633,7 +653,7 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
             for (int nb = 0; nb < NB; ++nb) {
                 float p[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(sv[nb][e] - m_run[nb]);
+                for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(pd[nb][e]);
                 l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
                 const float2v lo = {p[0] * t.vs, p[1] * t.vs}, hi = {p[2] * t.vs, p[3] * t.vs};
                 uint2 pk;
