@@ -326,6 +326,9 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                     f = __hip_atomic_load(&dep_flag[wslot + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
                 to_end = f == 2;
+                // (the deposit is read after the flag: the hardware serves a wave's LDS requests in order; this
+                // keeps the compiler from moving the reads ahead of the loop, at no instruction)
+                asm volatile("" ::: "memory");
                 const float4v *dq = dep_o[wslot + 1];
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
@@ -366,8 +369,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 }
                 // The slot's contents are in LDS before the flag says so: LDS serves a wave's requests in order,
                 // and the wait below covers LDS only (a release fence would also wait for the tiles in flight).
+                asm volatile("" ::: "memory");        // (the compiler keeps the deposit's stores above this line)
                 __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
                 __builtin_amdgcn_wave_barrier();
+                asm volatile("" ::: "memory");
                 if (lane == 0) __hip_atomic_store(&dep_flag[wslot], to_end ? 2 : 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 return;
             }
