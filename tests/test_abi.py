@@ -101,5 +101,9 @@ def test_options(L):
     assert L.ss_set_option(b"attn_path", 0) == 0
     assert L.ss_set_option(b"attn_path", 9) == 1
     assert L.ss_set_option(b"attn_waves", 6) == 1      # not a multiple of the workgroup's wave count
+    assert L.ss_set_option(b"attn_unit_weight", 65) == 1   # outside 0..64
+    assert L.ss_set_option(b"attn_unit_weight", -1) == 1
+    assert L.ss_set_option(b"attn_unit_weight", 0) == 0
+    assert L.ss_set_option(b"attn_unit_weight", 3) == 0    # back to the default
     assert L.ss_set_option(b"no_such_option", 1) == 1
     assert L.ss_set_option(None, 1) == 1

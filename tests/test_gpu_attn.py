@@ -84,6 +84,22 @@ def test_partition_count_invariance(oracle):
         binding.ss_set_option("attn_waves", 0)
 
 
+def test_span_cut_weight_invariance(oracle):
+    # where the spans are cut (what opening a unit is charged, in tiles) must not show in the result: many short
+    # units, a few long ones, several span counts -- cuts inside units, at unit starts and several units per span
+    cfg = LLAMA8B.scaled(batch=24, ctx=("loguniform", 17, 4000), depth=("uniform", 0, 8))
+    inp = synth.make_attention_inputs(cfg, seed=11)
+    try:
+        for weight in (0, 1, 3, 17, 64):
+            binding.ss_set_option("attn_unit_weight", weight)
+            for waves in (8, 64, 0):
+                binding.ss_set_option("attn_waves", waves)
+                check(inp, oracle, label=f"unit weight {weight}, waves {waves}")
+    finally:
+        binding.ss_set_option("attn_unit_weight", 3)
+        binding.ss_set_option("attn_waves", 0)
+
+
 def test_edge_lengths(oracle):
     # kv_len equal to q_len (nothing but the new tokens), exact multiples of the block size, one token
     kv_len = np.array([1, 9, 16, 17, 32, 5, 48, 255, 256, 257], np.int32)
