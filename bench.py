@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
-ATTN_SOURCES = ("attn_mfma_kernels.h", "attn_mfma.hip", "common.h", "tree_window.h")
+ATTN_SOURCES = ("attn_mfma_kernels.h", "attn_mfma.hip", "common.h", "tree_window.h", "span_cuts.h")
 
 
 def attn_source_hash() -> str:

@@ -21,6 +21,7 @@
 // the eight M-blocks of O^T are the eight interleaved d-phases, so no transpose through LDS is
 // needed (only a 16-bit pack per operand register).
 #include "common.h"
+#include "span_cuts.h"
 
 namespace ss {
 namespace {
@@ -37,35 +38,6 @@ namespace {
 // tile.  The cuts depend on the batch's lengths only, so results do not vary from run to run.
 // ---------------------------------------------------------------------------------------------
 constexpr int kPlanMaxBatch = 4096;   // requests whose tile prefix fits the plan kernel's LDS; beyond that the cuts are unweighted
-
-struct WeightedSpace {
-    const int32_t *prefix;   // [batch+1] exclusive prefix of tiles per kv head
-    int batch, hkv, weight;
-    long long total_w;       // tiles of all units plus weight per unit
-    int nw;
-    __device__ long long wave_start(long long w) const { return w * total_w / nw; }   // weighted coordinate of wave w's cut
-    __device__ long long unit_start(int b, int g) const   // weighted coordinate of unit (b, g)
-    {
-        const int n = prefix[b + 1] - prefix[b];
-        return ((long long)prefix[b] + (long long)weight * b) * hkv + (long long)g * (n + weight);
-    }
-    // unit and tile that weighted coordinate y (< total_w) falls on, and the flat tile index
-    __device__ long long locate(long long y, int &b, int &g, int &tile) const
-    {
-        int lo = 0, hi = batch - 1;   // last request whose first unit starts at or before y
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (((long long)prefix[mid] + (long long)weight * mid) * hkv <= y) lo = mid; else hi = mid - 1;
-        }
-        b = lo;
-        const int n = prefix[b + 1] - prefix[b];
-        const long long r = y - ((long long)prefix[b] + (long long)weight * b) * hkv;
-        g = (int)(r / (n + weight));
-        const int in_unit = (int)(r - (long long)g * (n + weight)) - weight;
-        tile = in_unit > 0 ? in_unit : 0;
-        return (long long)prefix[b] * hkv + (long long)g * n + tile;
-    }
-};
 
 __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
 {
@@ -134,26 +106,24 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(AttnArgs a)
     for (int t = tid; t < n; t += 256) dst[t] = bt[t] * a.num_kv_heads + g;
 
     // waves whose cut falls into this unit's stretch [ya, ya + weight + n) of the weighted coordinate
-    const WeightedSpace ws{prefix, a.batch, a.num_kv_heads, weight, total_w, (int)nw};
+    SpanCuts cuts;
+    cuts.prefix = prefix;   // (only read when weight > 0, i.e. when the prefix was built)
+    cuts.batch = a.batch;
+    cuts.hkv = a.num_kv_heads;
+    cuts.weight = weight;
+    cuts.total = total;
+    cuts.total_w = total_w;
+    cuts.nw = nw;
     const long long ya = off + (long long)weight * ((long long)b * a.num_kv_heads + g);
-    const long long w_lo = (ya * nw + total_w - 1) / total_w;                   // first w with w*total_w/nw >= ya
-    const long long w_hi = ((ya + weight + n) * nw + total_w - 1) / total_w;    // first w at or past the unit's end
+    const long long w_lo = cuts.first_cut_at_or_after(ya);                // first w with w*total_w/nw >= ya
+    const long long w_hi = cuts.first_cut_at_or_after(ya + weight + n);   // first w at or past the unit's end
     // Descriptor: {request, kv head, first tile, tiles of the unit, span begin, span end, kv_len,
     // first query row, end query row, addresses of the span's first kDescAddrs tiles}: everything
     // the wave's first loads depend on, so that they go out after a single read.
     for (long long w = w_lo + tid; w < w_hi && w < nw; w += 256) {
-        const long long in_unit = w * total_w / nw - ya - weight;
-        const int t0 = in_unit > 0 ? (int)in_unit : 0;
+        const int t0 = cuts.first_tile(cuts.cut(w), ya);
         const long long x0 = off + t0;
-        long long x1 = total;
-        if (w + 1 < nw) {
-            if (weight) {
-                int b1, g1, t1;
-                x1 = ws.locate((w + 1) * total_w / nw, b1, g1, t1);
-            } else {
-                x1 = (w + 1) * total / nw;
-            }
-        }
+        const long long x1 = cuts.span_end(w);
         int32_t *d = a.wave_desc + w * kDescInts;
         d[0] = b; d[1] = g; d[2] = t0; d[3] = n;
         d[4] = (int)x0; d[5] = (int)x1;

@@ -35,6 +35,7 @@
 #include <hip/hip_ext.h>
 
 #include "common.h"
+#include "span_cuts.h"
 #include "tree_window.h"
 
 namespace ss {
@@ -769,11 +770,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
     // its own); the last wave whose cut lies at or before coordinate t is ((t+1)*nw - 1) / total_w.  A cut
     // inside the unit's virtual part starts at its first tile, so the unit's first wave is the last one at
     // or before the end of that part, its last wave the last one before the next unit's stretch.
-    const long long weight = a.plan->unit_weight;
-    const long long total_w = total + weight * a.batch * a.num_kv_heads;
-    const long long ya = off + weight * unit;
-    int w_first = (int)(((ya + weight + 1) * nw - 1) / total_w);
-    int w_last = (int)(((ya + weight + nb_tiles) * nw - 1) / total_w);
+    SpanCuts cuts;
+    cuts.prefix = a.tile_prefix;
+    cuts.batch = a.batch;
+    cuts.hkv = a.num_kv_heads;
+    cuts.weight = a.plan->unit_weight;
+    cuts.total = total;
+    cuts.total_w = total + (long long)cuts.weight * a.batch * a.num_kv_heads;
+    cuts.nw = nw;
+    int w_first, w_last;
+    cuts.unit_waves(off + (long long)cuts.weight * unit, nb_tiles, w_first, w_last);
     if (a.chain) {
         // the streaming kernel has combined the spans of each workgroup: one partial per workgroup the unit
         // touches, and a unit inside a single workgroup is already finished
