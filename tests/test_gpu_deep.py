@@ -95,6 +95,13 @@ def test_batches_larger_than_a_workgroup(oracle):
     assert np.array_equal(d["kv_len"].cpu().numpy(), oracle.kv_commit(inp["q_indptr"], n.cpu().numpy(), inp["kv_len"]))
 
 
+def test_batch_beyond_the_plan_kernels_prefix_buffer(oracle):
+    # more than 4096 requests: the plan kernel cannot hold the tile prefix in LDS and cuts the spans unweighted
+    cfg = LLAMA8B.scaled(batch=4300, num_q_heads=8, num_kv_heads=2, ctx=("uniform", 3, 40), depth=("uniform", 0, 2))
+    inp = synth.make_attention_inputs(cfg, seed=8)
+    check(inp, oracle, label="4300 requests")
+
+
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("hq,hkv", [(8, 8), (8, 4), (16, 4), (16, 2)], ids=["g1", "g2", "g4", "g8"])
 def test_tree_depth_20_tail_slots_stay_invisible(oracle, kv_dtype, hq, hkv):
