@@ -3,13 +3,15 @@
 // Work decomposition.  The KV cache of one (request, KV head) pair ("unit") is a run of
 // 16-token tiles, one per cache block.  All tiles of all units form one flat sequence (unit
 // major).  A plan kernel writes that sequence out as a flat list of tile addresses (physical
-// block * kv heads + kv head) and cuts it into `num_waves` equal contiguous spans; every
-// wavefront streams one span, so the load is balanced whatever the mix of context lengths, and
-// the load side of the kernel is a plain linear walk that never stops at a unit boundary.  A
-// span may cover the tail of one unit, several whole units and the head of another; for every
-// unit it touches the wave emits one partial result (softmax reference, sum, unnormalised
-// output) into slot `wave + unit` (that sum is unique along the sequence).  A last kernel
-// merges the partials of each unit by their log-sum-exp and writes the rounded output.
+// block * kv heads + kv head) and cuts it into `num_waves` contiguous spans of equal cost (a
+// tile costs one, opening a unit a fixed number of tiles; span_cuts.h); every wavefront streams
+// one span, so the load is balanced whatever the mix of context lengths, and the load side of
+// the kernel is a plain linear walk that never stops at a unit boundary.  A span may cover the
+// tail of one unit, several whole units and the head of another; for every unit it touches the
+// wave has one partial result (softmax reference, sum, unnormalised output).  What the streaming
+// kernel cannot finish itself (attn_mfma_kernels.h) goes to a partial slot, `wave + unit` or
+// `workgroup + unit` (unique along the sequence), and a last kernel merges the partials of each
+// such unit by their log-sum-exp and writes the rounded output.
 //
 // Per tile, with rows = (k+1) * (query heads per KV head) padded to a multiple of 16:
 //   S^T[token][row] = K[token][:] . Q[row][:]   v_mfma_f32_16x16x32_bf16, K tile as A operand
