@@ -469,10 +469,10 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
     // unit's rows hold zero queries; they are computed anyway (cheaper than branching, which was
     // measured) and never stored.  Three wave-uniform branches leave the straight line: the mask
     // selects (only tiles that reach into the request's new tokens), the clearing of V slots past the
-    // end of the cache (e4m3 instances: only a cache's last tile) and the rare rescale.  Where a branch
-    // sits between matrix instructions and the first read of their result, or the read is written out
-    // by hand, explicit wait states stand in front of the read (the compiler's own bookkeeping of them
-    // is not relied on across blocks).
+    // end of the cache (e4m3 instances: only a cache's last tile) and the rare rescale.  The compiler
+    // keeps the wait states between a matrix instruction and the first read of its result, also across
+    // these branches; where the read is written out by hand (the rescale, from_accumulator_file) or
+    // follows a scheduling barrier (the end of a unit), explicit wait states stand in front of it.
     // The order of the pieces is chosen so that vector work that does not depend on a matrix result
     // follows each group of MFMAs: the V operands are built while S^T is in the matrix pipeline, and
     // a row block's exponentials while the previous block's output MFMAs run.
@@ -563,7 +563,6 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
         // at once; the scores themselves are only formed on the rare path (before a unit's first tile the
         // reference is so low that the argument has absorbed them).
         const float kscale = sc2 * t.ks;
-        if constexpr (FP8) accumulator_read_guard();   // the branch above separates the score MFMAs from these reads
         float pd[NB][4];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
