@@ -36,7 +36,25 @@ def _run(cmd, verbose):
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     lines = [l for l in res.stderr.splitlines() if NOISE not in l]
-    err = "\n".join(l for l in lines if "remark:" not in l)
+    # what is left for the log: everything but the resource remarks with their "included from" headers and
+    # source excerpts (the lines between a remark and the next diagnostic)
+    kept, in_remark = [], False
+    for l in lines:
+        if "remark:" in l:
+            in_remark = True
+            while kept and kept[-1].startswith("In file included from"):
+                kept.pop()
+            continue
+        if in_remark and (l.startswith(" ") or l.startswith("In file included from") or not l.strip()):
+            if l.startswith("In file included from"):
+                kept.append(l)   # may belong to a real diagnostic that follows; dropped again if a remark does
+                in_remark = False
+            continue
+        in_remark = False
+        kept.append(l)
+    while kept and kept[-1].startswith("In file included from"):
+        kept.pop()
+    err = "\n".join(kept)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + err)
     return err, _resources(lines)
