@@ -19,14 +19,17 @@ namespace {
 // A request needs one round per rejection, at most k; the launcher runs max_q_len - 1 rounds, a last
 // walk, sums and resid for the draws, and the pick.  r lives unnormalised in device memory (value / norm),
 // two fp64 vocabulary vectors per request.  All reductions have a fixed order.
-struct TreeState {
+struct TreeScalars {
     int32_t cur, n, next, phase;       // phase: 0 walking, 1 residual due, 2 draw due
     int32_t pure, degenerate, which, rej;   // which: the buffer that holds r; rej: the child just rejected
     float mp, mq;                      // exact maxima of the current node's target row / the rejected child's draft row
     double zp_stats;                   // normaliser of the target row from the first pass (judging only)
     double norm;                       // exact normaliser of the buffer that holds r
-    int32_t tok[SS_OUT_WIDTH];
-    int32_t node[SS_MAX_DEPTH];
+};
+struct TreeState {
+    TreeScalars s;                     // copied to registers by the kernels
+    int32_t tok[SS_OUT_WIDTH];         // accepted tokens and nodes so far: written and read in place (a private copy
+    int32_t node[SS_MAX_DEPTH];        // indexed by a run-time value would live in scratch memory)
 };
 
 enum { TS_WALK = 0, TS_RESIDUAL = 1, TS_DRAW = 2 };
@@ -60,14 +63,14 @@ __global__ __launch_bounds__(64) void tree_walk_kernel(AcceptArgs a, Workspace w
     const int t0 = a.q_indptr[b], k = a.q_indptr[b + 1] - t0 - 1, d0 = t0 - b;
     const float T = a.temperature ? a.temperature[b] : a.temperature_scalar;
     const double inv_t = 1.0 / (double)T;
-    TreeState s;
+    TreeScalars s;
     if (first) {
         s.cur = 0; s.n = 0; s.next = 1; s.phase = TS_WALK; s.pure = 1; s.degenerate = 0; s.which = 0; s.rej = 0;
         s.mq = 0.f; s.norm = 1.0;
         tree_row_stats(w, t0, inv_t, s.mp, s.zp_stats);
         if (lane < k && a.ratio_out) a.ratio_out[d0 + lane] = __builtin_nanf("");
     } else {
-        s = st[b];   // (every lane reads the same record; only lane 0 writes it back)
+        s = st[b].s;   // (every lane reads the same record; only lane 0 writes it back)
         if (s.phase == TS_DRAW) return;
     }
     if (s.phase == TS_RESIDUAL) {   // the residual of the last rejection is in the other buffer: adopt it
@@ -95,8 +98,10 @@ __global__ __launch_bounds__(64) void tree_walk_kernel(AcceptArgs a, Workspace w
                                  : r_arr[x] / s.norm;
         if (lane == 0 && a.ratio_out) a.ratio_out[d0 + c - 1] = (float)(rx / qx);
         if (u * qx < rx) {
-            s.tok[s.n] = x;
-            s.node[s.n] = c;
+            if (lane == 0) {
+                st[b].tok[s.n] = x;
+                st[b].node[s.n] = c;
+            }
             ++s.n;
             s.cur = c;
             s.pure = 1;
@@ -111,7 +116,7 @@ __global__ __launch_bounds__(64) void tree_walk_kernel(AcceptArgs a, Workspace w
     }
     s.next = c + 1;
     if (s.phase == TS_WALK) s.phase = TS_DRAW;   // no child left
-    if (lane == 0) st[b] = s;
+    if (lane == 0) st[b].s = s;
 }
 
 // Exact block sums of exponentials: of the rejected child's proposal (residual due), of the current
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void tree_sums_kernel(AcceptArgs a, Works
     __shared__ double sh[4];
     __shared__ ExpTable ex;
     const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
-    const TreeState &s = st[b];
+    const TreeScalars s = st[b].s;
     const bool want_q = s.phase == TS_RESIDUAL && !final_pass;
     const bool want_p = s.pure && (want_q || (final_pass && s.phase == TS_DRAW && !s.degenerate));
     if (!want_q && !want_p) return;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void tree_resid_kernel(AcceptArgs a, Work
     __shared__ double sh[4];
     __shared__ ExpTable ex;
     const int sub = blockIdx.x % w.nsub, b = blockIdx.x / w.nsub, tid = threadIdx.x;
-    const TreeState &s = st[b];
+    const TreeScalars s = st[b].s;
     const bool resid = s.phase == TS_RESIDUAL && !final_pass;
     const bool draw = final_pass && s.phase == TS_DRAW && !s.degenerate;
     if (!resid && !draw) return;
@@ -212,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void tree_pick_kernel(AcceptArgs a, Works
     __shared__ double prefix_sh, total_sh, norm_sh;
     __shared__ double mass_sh[kThreads];
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const TreeState s = st[b];
+    const TreeScalars s = st[b].s;
     const int V = a.vocab;
     const int t0 = a.q_indptr[b];
     const int64_t ob = (int64_t)b * w.nsub;
@@ -323,8 +328,8 @@ __global__ __launch_bounds__(kThreads) void tree_pick_kernel(AcceptArgs a, Works
         y = first == 0x7fffffff ? last_tok : max(max(shi[0], shi[1]), max(shi[2], shi[3]));
     }
     if (tid < SS_OUT_WIDTH)
-        a.out_tokens[(int64_t)b * SS_OUT_WIDTH + tid] = tid < s.n ? s.tok[tid] : (tid == s.n ? y : -1);
-    if (tid < SS_MAX_DEPTH) a.accepted_nodes[(int64_t)b * SS_MAX_DEPTH + tid] = tid < s.n ? s.node[tid] : -1;
+        a.out_tokens[(int64_t)b * SS_OUT_WIDTH + tid] = tid < s.n ? st[b].tok[tid] : (tid == s.n ? y : -1);
+    if (tid < SS_MAX_DEPTH) a.accepted_nodes[(int64_t)b * SS_MAX_DEPTH + tid] = tid < s.n ? st[b].node[tid] : -1;
     if (tid == 0) a.accepted_len[b] = s.n;
 }
 
