@@ -184,6 +184,7 @@ __global__ __launch_bounds__(kThreads) void tree_resid_kernel(AcceptArgs a, Work
         for (int c = 0; c < w.nsub; ++c) norm += w.zp[ob + c];
     }
     double *cur_arr = arr + ((int64_t)b * 2 + s.which) * V, *alt = arr + ((int64_t)b * 2 + (s.which ^ 1)) * V;
+    const double inv_norm = 1.0 / norm, inv_zq = 1.0 / zq;   // (one division each instead of two per vocabulary entry)
     double sum = 0.0;
 #pragma unroll
     for (int j = 0; j < kSubPer; ++j) {
@@ -191,9 +192,9 @@ __global__ __launch_bounds__(kThreads) void tree_resid_kernel(AcceptArgs a, Work
         if (v < V) {
             const double e = s.pure ? ex(((double)load_logit(a.target, t0 + s.cur, a.row_stride, DT, v) - (double)s.mp) * inv_t)
                                     : cur_arr[v];
-            const double rt = e / norm;
+            const double rt = e * inv_norm;
             if (resid) {
-                const double qt = ex(((double)load_logit(a.draft, d0 + s.rej - 1, a.row_stride, DT, v) - (double)s.mq) * inv_t) / zq;
+                const double qt = ex(((double)load_logit(a.draft, d0 + s.rej - 1, a.row_stride, DT, v) - (double)s.mq) * inv_t) * inv_zq;
                 const double res = rt > qt ? rt - qt : 0.0;
                 alt[v] = res;
                 sum += res;
