@@ -170,9 +170,9 @@ __global__ __launch_bounds__(kThreads) void accept_rowstats_kernel(AcceptArgs a,
 }
 
 // ---- decide ---------------------------------------------------------------------------------
-// One 256-lane workgroup per request.  Wave wv merges the chunk statistics of rows wv, wv+4, ...
-// (lanes over chunks), then lanes 0..k-1 of wave 0 evaluate their draft and a ballot finds the
-// first rejection.
+// One 256-lane workgroup per request.  Each quarter of a wavefront merges the chunk statistics of one row
+// (16 lanes over the chunks; 16 rows per trip), then lanes 0..k-1 of wave 0 evaluate their draft and a
+// ballot finds the first rejection.
 __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, Workspace w)
 {
     __shared__ float row_m[kMaxRows];
@@ -197,26 +197,34 @@ __global__ __launch_bounds__(kThreads) void accept_decide_kernel(AcceptArgs a, W
         }
     }
 
-    for (int j = wave; j < nrows; j += 4) {
-        const int64_t ry = j <= k ? (int64_t)t0 + j : (int64_t)a.total_rows + d0 + (j - k - 1);
+    // Sixteen rows at a time: every quarter of a wavefront (16 lanes over the chunks) merges one row, so the
+    // rows of an ordinary request are done in one trip.
+    const int quarter = lane >> 4, ql = lane & 15;
+    for (int j0 = 0; j0 < nrows; j0 += 16) {
+        const int j = j0 + wave * 4 + quarter;
+        const bool live = j < nrows;
+        const int64_t ry = !live ? 0 : (j <= k ? (int64_t)t0 + j : (int64_t)a.total_rows + d0 + (j - k - 1));
         float m = -INFINITY;
-        for (int c = lane; c < w.nchunks; c += 64) m = fmaxf(m, w.cmax[ry * w.nchunks + c]);
-        for (int off = 32; off; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+        if (live)
+            for (int c = ql; c < w.nchunks; c += 16) m = fmaxf(m, w.cmax[ry * w.nchunks + c]);
+        for (int off = 8; off; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));   // (stays inside the quarter)
         if (a.greedy) {
             int best = 0x7fffffff;
-            for (int c = lane; c < w.nchunks; c += 64)
-                if (w.cmax[ry * w.nchunks + c] == m) best = min(best, w.carg[ry * w.nchunks + c]);
-            for (int off = 32; off; off >>= 1) best = min(best, __shfl_xor(best, off));
-            if (lane == 0) row_arg[j] = best;
+            if (live)
+                for (int c = ql; c < w.nchunks; c += 16)
+                    if (w.cmax[ry * w.nchunks + c] == m) best = min(best, w.carg[ry * w.nchunks + c]);
+            for (int off = 8; off; off >>= 1) best = min(best, __shfl_xor(best, off));
+            if (live && ql == 0) row_arg[j] = best;
         } else {
             double z = 0.0;
-            for (int c = lane; c < w.nchunks; c += 64) {
-                const float cm = w.cmax[ry * w.nchunks + c];
-                if (cm != -INFINITY)
-                    z += (double)w.csum[ry * w.nchunks + c] * exp2(((double)cm - (double)m) * inv_t * kLog2eD);
-            }
-            for (int off = 32; off; off >>= 1) z += __shfl_xor(z, off);
-            if (lane == 0) {
+            if (live)
+                for (int c = ql; c < w.nchunks; c += 16) {
+                    const float cm = w.cmax[ry * w.nchunks + c];
+                    if (cm != -INFINITY)
+                        z += (double)w.csum[ry * w.nchunks + c] * exp2(((double)cm - (double)m) * inv_t * kLog2eD);
+                }
+            for (int off = 8; off; off >>= 1) z += __shfl_xor(z, off);
+            if (live && ql == 0) {
                 row_m[j] = m;
                 row_z[j] = z;
             }
