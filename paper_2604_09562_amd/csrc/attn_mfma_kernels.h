@@ -53,6 +53,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 8.0f;       // log2 headroom of the lagging softmax reference
 constexpr float kNoMax = -1.0e30f;   // reference before any score was seen (finite, so that -inf - ref stays -inf)
 constexpr int kIdWindow = 512;       // tile addresses a wave stages in LDS at a time
+constexpr int kMaxFlagPolls = 1 << 23;   // polls of a neighbour's deposit flag before giving up (each at least 128 cycles)
 constexpr int kPartRowStride = 33;   // float4 per staged partial row in LDS (32 of data + 1 of padding)
 template <int NB>
 constexpr bool kChainMerge = NB <= 2;   // instances that combine the spans of a workgroup in LDS
@@ -321,10 +322,17 @@ __global__ __launch_bounds__(64 * kWavesPerWg, 1) void attn_stream_kernel(
                 // segment: finished long ago unless the spans are very short.  Fold its result into mine
                 // (mine first: a fixed order, so the bits do not depend on timing).
                 // (relaxed LDS accesses: a volatile or acquiring load would first wait for every tile in flight)
+                // The wait is bounded (about a second): the neighbour is a wave of the same workgroup and reaches its
+                // deposit without waiting for anything itself, so the bound is never met; if it ever were, the unit's
+                // rows come out as NaN instead of the kernel hanging.
                 int f = __hip_atomic_load(&dep_flag[wslot + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                while (f == 0) {
+                for (int polls = 0; f == 0 && polls < kMaxFlagPolls; ++polls) {
                     __builtin_amdgcn_s_sleep(2);
                     f = __hip_atomic_load(&dep_flag[wslot + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                if (f == 0) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) lsum[nb] = __builtin_nanf("");
                 }
                 to_end = f == 2;
                 // (the deposit is read after the flag: the hardware serves a wave's LDS requests in order; this
